@@ -1,0 +1,159 @@
+/*
+ * bitstack.h -- C ABI of the MI355X (gfx950) BitStack linear-layer library.
+ *
+ * A weight matrix W_t (out x in, PyTorch-linear orientation, y = W_t x) is held
+ * as a stack of n residual blocks (BitStack, arxiv 2410.23918, Section 2.1):
+ * block i is a +-1 sign matrix S_i (1 bit per weight, packed), and two rank-k
+ * fp16 magnitude factors U_i (out x k) and V_i (in x k); a positive scale
+ * vector s (one entry per input channel) comes from activation-aware scaling.
+ * With the first n_loaded blocks resident the layer computes
+ *
+ *     y = ( sum_{i < n_loaded} S_i (.) (U_i V_i^T) ) diag(1/s) x        (Eq. 4, Eq. 8)
+ *
+ * without ever writing the reconstructed weight to device memory.
+ * (Paper orientation: X (p x m), W (m x n), Y = X W; here out = n_paper,
+ *  in = m_paper, U = B', V = A', S = W_sign^T.)
+ *
+ * Conventions for every function
+ *   - returns 0 (BITSTACK_OK) or a negative BITSTACK_E* code; never throws,
+ *     never aborts; bitstack_strerror() names the code.
+ *   - pointers marked "host" are ordinary host memory, "device" are HIP device
+ *     pointers on the current device.  The library never allocates or frees
+ *     device memory: all of it is owned by the caller (e.g. a torch tensor),
+ *     which must keep it alive while a handle points into it.
+ *   - fp16 values cross the ABI as raw IEEE binary16 bit patterns (uint16_t).
+ *   - supported shapes: k == 16, in % 256 == 0, out % 32 == 0.
+ *
+ * Canonical sign packing (the bit-exact interchange format; the paper only says
+ * the sign matrix is packed into an integer type, Section 2.1.2 / Fig. 3):
+ * uint32 words, row-major [block][out][in/32]; bit b of word w of a row is
+ * column 32*w + b; bit value 1 <=> S = +1; sign(0) = sign(-0) = +1.
+ * The layout inside the device buffer is private to the library and round-trips
+ * to the canonical form through bitstack_unpack_blocks().
+ */
+#ifndef BITSTACK_H
+#define BITSTACK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* hipStream_t is an opaque pointer; declared as void* so that this header does
+ * not need the HIP headers.  NULL is the default stream. */
+typedef void* bitstack_stream_t;
+
+typedef struct bitstack_weight bitstack_weight_t; /* host handle of one packed stack */
+
+enum {
+    BITSTACK_OK        = 0,
+    BITSTACK_E_NULL    = -1, /* a required pointer is NULL                        */
+    BITSTACK_E_SHAPE   = -2, /* k != 16, in % 256, out % 32, or non-positive dims */
+    BITSTACK_E_RANGE   = -3, /* n_loaded outside [0, n], batch outside [1, max]   */
+    BITSTACK_E_ALIGN   = -4, /* device pointer not 16-byte (x, y) / 256-byte (buf) aligned */
+    BITSTACK_E_SCALE   = -5, /* an entry of s is not finite or not > 0            */
+    BITSTACK_E_BUFSIZE = -6, /* buffer smaller than bitstack_packed_bytes()       */
+    BITSTACK_E_HIP     = -7, /* a HIP runtime call failed: bitstack_last_hip_error() */
+    BITSTACK_E_ARG     = -8  /* unknown dtype / kernel selector                   */
+};
+
+/* output element types for bitstack_linear_batched */
+enum { BITSTACK_Y_F16 = 0, BITSTACK_Y_F32 = 1 };
+
+/* kernel selectors (bitstack_linear_select); AUTO is what bitstack_linear uses */
+enum {
+    BITSTACK_KERNEL_AUTO      = 0,
+    BITSTACK_KERNEL_REFERENCE = 1, /* plain vector-ALU kernel, any batch <= max_batch */
+    BITSTACK_KERNEL_DECODE    = 2, /* matrix-core sign-stream kernel, batch 1         */
+    BITSTACK_KERNEL_PANEL     = 3  /* tile-reconstructing matrix-core kernel, batch >= 2 */
+};
+
+/* Bytes of one residual block: (out*in + 16*k*(out+in)) / 8, Eq. (9) of the
+ * appendix on minimal transmission units.  This is the "block-stream" byte count
+ * of the throughput metric.  Returns 0 for unsupported shapes. */
+size_t bitstack_block_bytes(int out, int in, int k);
+
+/* Device bytes bitstack_pack_blocks needs for a stack of n blocks: 1/s, the n
+ * blocks (each contiguous and self-contained, exactly bitstack_block_bytes long)
+ * and an accumulation workspace for max_batch tokens.  0 for unsupported shapes. */
+size_t bitstack_packed_bytes(int out, int in, int k, int n, int max_batch);
+
+/* Host only.  Canonical packing of the sign matrix of a float residual:
+ * bit = 1 where residual >= 0 (Section 2.1.2: W = W_sign (.) |W|, W_sign in {+-1}).
+ * residual: host [out][in] float32; sign_words: host [out][in/32] uint32 (written). */
+int bitstack_pack_signs_from_f32(int out, int in, const float* residual, uint32_t* sign_words);
+
+/* Host only.  Builds the private device image of a whole stack in host memory
+ * (what bitstack_pack_blocks copies to the device).  Lets the layout be tested
+ * without a GPU.
+ *   sign_words host [n][out][in/32] canonical; U host [n][out][k]; V host [n][in][k];
+ *   s host [in], every entry finite and > 0; image host, image_bytes >=
+ *   bitstack_packed_bytes(out,in,k,n,max_batch). */
+int bitstack_pack_image_host(int out, int in, int k, int n, int max_batch,
+                             const uint32_t* sign_words, const uint16_t* U, const uint16_t* V,
+                             const float* s, void* image, size_t image_bytes);
+
+/* Host only.  Inverse of bitstack_pack_image_host for one block: image ->
+ * canonical sign words, U, V (any output pointer may be NULL to skip it). */
+int bitstack_unpack_image_host(int out, int in, int k, int n, int max_batch,
+                               const void* image, int block,
+                               uint32_t* sign_words, uint16_t* U, uint16_t* V);
+
+/* Packs a stack into caller-owned device memory and returns a handle
+ * (Section 2: residual blocks are the units that are loaded into memory; a
+ * weight is a stack of them, loaded in order).
+ *   device_buf: device, 256-byte aligned, device_buf_bytes >= bitstack_packed_bytes().
+ *   stream: copies are enqueued here and the stream is synchronised before return.
+ *   handle: receives a library-owned host object; free it with bitstack_release().
+ * The workspace part of the buffer is zeroed.  Two bitstack_linear calls that
+ * use the same handle must not overlap in time (they share that workspace). */
+int bitstack_pack_blocks(int out, int in, int k, int n, int max_batch,
+                         const uint32_t* sign_words, const uint16_t* U, const uint16_t* V,
+                         const float* s,
+                         void* device_buf, size_t device_buf_bytes,
+                         bitstack_stream_t stream, bitstack_weight_t** handle);
+
+/* Device layout -> canonical form for one block (for bit-exactness tests).
+ * Outputs are host arrays (NULL to skip).  Synchronises the stream. */
+int bitstack_unpack_blocks(const bitstack_weight_t* w, int block,
+                           uint32_t* sign_words, uint16_t* U, uint16_t* V,
+                           bitstack_stream_t stream);
+
+/* The forward pass for one token (batch-1 decode):
+ *   y = ( sum_{i < n_loaded} S_i (.) (U_i V_i^T) ) diag(1/s) x           (Eq. 4 + Eq. 8)
+ *   x: device fp16 [in], 16-byte aligned.   y: device fp16 [out], 16-byte aligned.
+ *   n_loaded in [0, n]: the loaded prefix of the stack; 0 gives y = 0.
+ * Asynchronous: work is enqueued on stream and the call returns. */
+int bitstack_linear(const void* x, const bitstack_weight_t* blocks, int n_loaded,
+                    void* y, bitstack_stream_t stream);
+
+/* Same for a batch of tokens.  x: device fp16 [batch][in] row-major;
+ * y: device [batch][out] row-major of y_dtype (BITSTACK_Y_F16 / BITSTACK_Y_F32);
+ * 1 <= batch <= max_batch given at pack time. */
+int bitstack_linear_batched(const void* x, int batch, const bitstack_weight_t* blocks,
+                            int n_loaded, void* y, int y_dtype, bitstack_stream_t stream);
+
+/* As bitstack_linear_batched with an explicit kernel choice (tests, benchmarks).
+ * Returns BITSTACK_E_ARG when the chosen kernel does not support the batch. */
+int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* blocks,
+                           int n_loaded, void* y, int y_dtype, int kernel,
+                           bitstack_stream_t stream);
+
+/* Shape queries on a handle. */
+int bitstack_weight_shape(const bitstack_weight_t* w, int* out, int* in, int* k, int* n,
+                          int* max_batch);
+
+/* Frees the host handle only; the device buffer stays the caller's. */
+void bitstack_release(bitstack_weight_t* w);
+
+const char* bitstack_strerror(int code);
+
+/* hipError_t value of the most recent failing HIP call on this thread (0 if none). */
+int bitstack_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITSTACK_H */
