@@ -129,6 +129,20 @@ int bitstack_unpack_blocks(const bitstack_weight_t* w, int block,
 int bitstack_linear(const void* x, const bitstack_weight_t* blocks, int n_loaded,
                     void* y, bitstack_stream_t stream);
 
+/* A sequence of batch-1 forward passes enqueued back to back on one stream from
+ * native code (one token through many linears, e.g. the 224 linears of a decoder,
+ * each with its own n_loaded as the sorted stack leaves them, Section 2.2).
+ * Equivalent to calling bitstack_linear(jobs[i].x, jobs[i].blocks, jobs[i].n_loaded,
+ * jobs[i].y, stream) for i = 0..count-1, the whole list `repeat` times.
+ * Stops at the first failing job and returns its error. */
+typedef struct bitstack_job {
+    const void* x;                   /* device fp16 [in]  */
+    const bitstack_weight_t* blocks; /* packed stack      */
+    int n_loaded;
+    void* y;                         /* device fp16 [out] */
+} bitstack_job_t;
+int bitstack_linear_many(const bitstack_job_t* jobs, int count, int repeat, bitstack_stream_t stream);
+
 /* Same for a batch of tokens.  x: device fp16 [batch][in] row-major;
  * y: device [batch][out] row-major of y_dtype (BITSTACK_Y_F16 / BITSTACK_Y_F32);
  * 1 <= batch <= max_batch given at pack time. */
@@ -140,6 +154,22 @@ int bitstack_linear_batched(const void* x, int batch, const bitstack_weight_t* b
 int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* blocks,
                            int n_loaded, void* y, int y_dtype, int kernel,
                            bitstack_stream_t stream);
+
+/* Tuning hooks for benchmarks (process-wide, not thread-safe).  value 0 restores
+ * the built-in choice.  Unknown options or unsupported values give BITSTACK_E_ARG
+ * (at the next launch for values). */
+enum {
+    BITSTACK_OPT_DECODE_WAVES = 1, /* wavefronts per workgroup of the decode kernel: 4, 8, 16 */
+    BITSTACK_OPT_DECODE_KSLAB = 2  /* input columns per workgroup: 256, 512, 1024, 2048      */
+};
+int bitstack_set_option(int option, int value);
+
+/* Measurement aid: reads device_buf[0, bytes) once with 128-bit loads (nothing is
+ * written unless the xor of the data hits one magic value).  Gives the achievable
+ * HBM read rate that the sign stream of the decode path is compared with.
+ * device_buf 16-byte aligned, bytes % 16 == 0, device_sink >= 4 bytes. */
+int bitstack_probe_read(const void* device_buf, size_t bytes, void* device_sink, int workgroups,
+                        bitstack_stream_t stream);
 
 /* Shape queries on a handle. */
 int bitstack_weight_shape(const bitstack_weight_t* w, int* out, int* in, int* k, int* n,

@@ -70,9 +70,10 @@ def pack_signs(sign: np.ndarray) -> np.ndarray:
         raise ValueError("in must be a multiple of 32 for the canonical packing")
     if not np.all((s == 1) | (s == -1)):
         raise ValueError("sign matrix must hold only +1/-1")
-    bits = (s > 0).astype(np.uint64).reshape(out, inn // 32, 32)
-    weights = (np.uint64(1) << np.arange(32, dtype=np.uint64))
-    return (bits * weights).sum(axis=2).astype(np.uint32)
+    # bit b of byte q <-> column 8 q + b; four consecutive bytes, least significant
+    # first, form one word
+    by = np.packbits(s > 0, axis=1, bitorder="little")
+    return np.ascontiguousarray(by).view("<u4").astype(np.uint32)
 
 
 def unpack_signs(words: np.ndarray, inn: int) -> np.ndarray:

@@ -1,0 +1,23 @@
+"""MI355X-native BitStack linear layer: thin ctypes binding over libbitstack.so.
+
+Every step of the forward pass runs inside the HIP library; this package only
+marshals arguments.  PyTorch supplies device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    BitStackError,
+    PackedStack,
+    KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL,
+    OPT_DECODE_WAVES, OPT_DECODE_KSLAB,
+    block_bytes,
+    lib,
+    linear_many,
+    make_jobs,
+    lib_path,
+    pack_image_host,
+    pack_signs_from_f32,
+    packed_bytes,
+    probe_read,
+    set_option,
+    strerror,
+    unpack_image_host,
+)

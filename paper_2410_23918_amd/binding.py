@@ -1,0 +1,236 @@
+"""ctypes binding with the same names as include/bitstack.h (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libbitstack.so")
+_lib = None
+
+KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL = 0, 1, 2, 3
+Y_F16, Y_F32 = 0, 1
+OPT_DECODE_WAVES, OPT_DECODE_KSLAB = 1, 2
+
+
+class BitStackError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = lib().bitstack_strerror(code).decode()
+        if code == -7:
+            msg += f" (hipError {lib().bitstack_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{code}]")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """Loads libbitstack.so; builds it first only if it is not there.  Fails loudly
+    (no fallback of any kind) when the library cannot be loaded."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from .build import build
+        build()
+    L = C.CDLL(_LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int, C.c_size_t
+    L.bitstack_block_bytes.restype = sz
+    L.bitstack_block_bytes.argtypes = [i32, i32, i32]
+    L.bitstack_packed_bytes.restype = sz
+    L.bitstack_packed_bytes.argtypes = [i32, i32, i32, i32, i32]
+    L.bitstack_pack_signs_from_f32.argtypes = [i32, i32, vp, vp]
+    L.bitstack_pack_image_host.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz]
+    L.bitstack_unpack_image_host.argtypes = [i32, i32, i32, i32, i32, vp, i32, vp, vp, vp]
+    L.bitstack_pack_blocks.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp, C.POINTER(vp)]
+    L.bitstack_unpack_blocks.argtypes = [vp, i32, vp, vp, vp, vp]
+    L.bitstack_linear.argtypes = [vp, vp, i32, vp, vp]
+    L.bitstack_linear_batched.argtypes = [vp, i32, vp, i32, vp, i32, vp]
+    L.bitstack_linear_select.argtypes = [vp, i32, vp, i32, vp, i32, i32, vp]
+    L.bitstack_weight_shape.argtypes = [vp] + [C.POINTER(i32)] * 5
+    L.bitstack_linear_many.argtypes = [vp, i32, i32, vp]
+    L.bitstack_linear_many.restype = i32
+    L.bitstack_set_option.argtypes = [i32, i32]
+    L.bitstack_probe_read.argtypes = [vp, sz, vp, i32, vp]
+    L.bitstack_probe_read.restype = i32
+    L.bitstack_release.argtypes = [vp]
+    L.bitstack_release.restype = None
+    L.bitstack_strerror.restype = C.c_char_p
+    L.bitstack_strerror.argtypes = [i32]
+    L.bitstack_last_hip_error.restype = i32
+    for name in ("bitstack_pack_signs_from_f32", "bitstack_pack_image_host", "bitstack_unpack_image_host",
+                 "bitstack_pack_blocks", "bitstack_unpack_blocks", "bitstack_linear",
+                 "bitstack_linear_batched", "bitstack_linear_select", "bitstack_weight_shape",
+                 "bitstack_set_option"):
+        getattr(L, name).restype = i32
+    _lib = L
+    return L
+
+
+class Job(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("blocks", C.c_void_p), ("n_loaded", C.c_int), ("y", C.c_void_p)]
+
+
+def make_jobs(items):
+    """items: iterable of (x tensor, PackedStack, n_loaded, y tensor) -> ctypes job array."""
+    items = list(items)
+    arr = (Job * len(items))()
+    for j, (x, ps, nl, y) in zip(arr, items):
+        j.x, j.blocks, j.n_loaded, j.y = x.data_ptr(), ps.handle.value, int(nl), y.data_ptr()
+    arr._keepalive = items
+    return arr
+
+
+def linear_many(jobs, repeat: int = 1, stream=None):
+    """bitstack_linear_many on a job array from make_jobs (current torch stream by default)."""
+    import torch
+    st = C.c_void_p((stream or torch.cuda.current_stream()).cuda_stream)
+    _check(lib().bitstack_linear_many(jobs, len(jobs), repeat, st), "bitstack_linear_many")
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise BitStackError(rc, where)
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def strerror(code: int) -> str:
+    return lib().bitstack_strerror(code).decode()
+
+
+def block_bytes(out: int, inn: int, k: int = 16) -> int:
+    return int(lib().bitstack_block_bytes(out, inn, k))
+
+
+def packed_bytes(out: int, inn: int, k: int, n: int, max_batch: int = 1) -> int:
+    return int(lib().bitstack_packed_bytes(out, inn, k, n, max_batch))
+
+
+def set_option(option: int, value: int):
+    _check(lib().bitstack_set_option(option, value), "bitstack_set_option")
+
+
+def probe_read(buf, sink, workgroups: int = 4096, stream=None):
+    """bitstack_probe_read on a torch uint8 tensor."""
+    import torch
+    st = C.c_void_p((stream or torch.cuda.current_stream(buf.device)).cuda_stream)
+    _check(lib().bitstack_probe_read(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), workgroups, st),
+           "bitstack_probe_read")
+
+
+def pack_signs_from_f32(residual: np.ndarray) -> np.ndarray:
+    r = np.ascontiguousarray(residual, dtype=np.float32)
+    out, inn = r.shape
+    words = np.empty((out, max(inn // 32, 0)), dtype=np.uint32)
+    _check(lib().bitstack_pack_signs_from_f32(out, inn, _ptr(r), _ptr(words)), "bitstack_pack_signs_from_f32")
+    return words
+
+
+def _canon(sign_words, U, V, s):
+    sw = np.ascontiguousarray(sign_words, dtype=np.uint32)
+    U = np.ascontiguousarray(U, dtype=np.float16)
+    V = np.ascontiguousarray(V, dtype=np.float16)
+    s = np.ascontiguousarray(s, dtype=np.float32)
+    n, out, k = U.shape
+    inn = V.shape[1]
+    assert sw.shape == (n, out, inn // 32) and V.shape == (n, inn, k) and s.shape == (inn,)
+    return sw, U, V, s, n, out, inn, k
+
+
+def pack_image_host(sign_words, U, V, s, max_batch: int = 1) -> np.ndarray:
+    sw, U, V, s, n, out, inn, k = _canon(sign_words, U, V, s)
+    nbytes = packed_bytes(out, inn, k, n, max_batch)
+    if nbytes == 0:
+        raise BitStackError(-2, "bitstack_packed_bytes")
+    img = np.empty(nbytes, dtype=np.uint8)
+    _check(lib().bitstack_pack_image_host(out, inn, k, n, max_batch, _ptr(sw), _ptr(U), _ptr(V), _ptr(s),
+                                          _ptr(img), nbytes), "bitstack_pack_image_host")
+    return img
+
+
+def unpack_image_host(img: np.ndarray, out: int, inn: int, k: int, n: int, max_batch: int, block: int):
+    sw = np.empty((out, inn // 32), dtype=np.uint32)
+    U = np.empty((out, k), dtype=np.float16)
+    V = np.empty((inn, k), dtype=np.float16)
+    _check(lib().bitstack_unpack_image_host(out, inn, k, n, max_batch, _ptr(img), block, _ptr(sw), _ptr(U), _ptr(V)),
+           "bitstack_unpack_image_host")
+    return sw, U, V
+
+
+class PackedStack:
+    """A weight stack resident in device memory (a torch uint8 tensor owned here)."""
+
+    def __init__(self, sign_words, U, V, s, max_batch: int = 1, device="cuda:0", stream=None):
+        import torch
+        sw, U, V, s, n, out, inn, k = _canon(sign_words, U, V, s)
+        self.out, self.inn, self.k, self.n, self.max_batch = out, inn, k, n, max_batch
+        nbytes = packed_bytes(out, inn, k, n, max_batch)
+        if nbytes == 0:
+            raise BitStackError(-2, "bitstack_packed_bytes")
+        self.device = torch.device(device)
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self._h = C.c_void_p()
+        st = self._stream(stream)
+        _check(lib().bitstack_pack_blocks(out, inn, k, n, max_batch, _ptr(sw), _ptr(U), _ptr(V), _ptr(s),
+                                          self.buf.data_ptr(), nbytes, st, C.byref(self._h)),
+               "bitstack_pack_blocks")
+
+    def _stream(self, stream):
+        import torch
+        if stream is None:
+            stream = torch.cuda.current_stream(self.device)
+        return C.c_void_p(stream.cuda_stream)
+
+    @property
+    def handle(self):
+        return self._h
+
+    @property
+    def block_bytes(self) -> int:
+        return block_bytes(self.out, self.inn, self.k)
+
+    def unpack_block(self, block: int, stream=None):
+        sw = np.empty((self.out, self.inn // 32), dtype=np.uint32)
+        U = np.empty((self.out, self.k), dtype=np.float16)
+        V = np.empty((self.inn, self.k), dtype=np.float16)
+        _check(lib().bitstack_unpack_blocks(self._h, block, _ptr(sw), _ptr(U), _ptr(V), self._stream(stream)),
+               "bitstack_unpack_blocks")
+        return sw, U, V
+
+    def linear(self, x, n_loaded: int, y=None, stream=None):
+        """bitstack_linear: one token, fp16 in, fp16 out."""
+        import torch
+        if y is None:
+            y = torch.empty(self.out, dtype=torch.float16, device=self.device)
+        _check(lib().bitstack_linear(x.data_ptr(), self._h, n_loaded, y.data_ptr(), self._stream(stream)),
+               "bitstack_linear")
+        return y
+
+    def linear_batched(self, x, n_loaded: int, y=None, out_dtype=None, kernel: int = KERNEL_AUTO, stream=None):
+        import torch
+        batch = x.shape[0]
+        out_dtype = out_dtype or (y.dtype if y is not None else torch.float16)
+        if y is None:
+            y = torch.empty((batch, self.out), dtype=out_dtype, device=self.device)
+        yd = Y_F32 if out_dtype == torch.float32 else Y_F16
+        _check(lib().bitstack_linear_select(x.data_ptr(), batch, self._h, n_loaded, y.data_ptr(), yd, kernel,
+                                            self._stream(stream)), "bitstack_linear_select")
+        return y
+
+    def release(self):
+        if self._h:
+            lib().bitstack_release(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.release()
+        except Exception:
+            pass

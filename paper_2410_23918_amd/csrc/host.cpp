@@ -1,0 +1,285 @@
+// Host side of the BitStack C ABI: argument checks, packing into the private
+// device layout, kernel dispatch.  See include/bitstack.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/bitstack.h"
+#include "kernels.h"
+#include "layout.h"
+
+using namespace bitstack;
+
+struct bitstack_weight {
+    Geometry geo;
+    unsigned char* dev;  // caller-owned device buffer
+};
+
+static thread_local int g_last_hip = 0;
+
+static int hip_fail(hipError_t e) {
+    g_last_hip = static_cast<int>(e);
+    return BITSTACK_E_HIP;
+}
+#define BS_HIP(call)                                   \
+    do {                                               \
+        hipError_t e__ = (call);                       \
+        if (e__ != hipSuccess) return hip_fail(e__);   \
+    } while (0)
+
+extern "C" {
+
+size_t bitstack_block_bytes(int out, int in, int k) {
+    if (!shape_ok(out, in, k)) return 0;
+    return (size_t(out) * size_t(in) + size_t(16) * k * (size_t(out) + size_t(in))) / 8;
+}
+
+size_t bitstack_packed_bytes(int out, int in, int k, int n, int max_batch) {
+    if (!shape_ok(out, in, k) || n < 0 || max_batch < 1) return 0;
+    return make_geometry(out, in, n, max_batch).total;
+}
+
+int bitstack_pack_signs_from_f32(int out, int in, const float* residual, uint32_t* sign_words) {
+    if (!residual || !sign_words) return BITSTACK_E_NULL;
+    if (out <= 0 || in <= 0 || in % 32) return BITSTACK_E_SHAPE;
+    const int wpr = in / 32;
+    for (int o = 0; o < out; ++o) {
+        const float* row = residual + size_t(o) * in;
+        for (int w = 0; w < wpr; ++w) {
+            uint32_t word = 0;
+            for (int b = 0; b < 32; ++b)
+                if (row[w * 32 + b] >= 0.0f) word |= (uint32_t(1) << b);  // +0, -0 -> +1
+            sign_words[size_t(o) * wpr + w] = word;
+        }
+    }
+    return BITSTACK_OK;
+}
+
+static int check_pack_args(int out, int in, int k, int n, int max_batch, const uint32_t* sw,
+                           const uint16_t* U, const uint16_t* V, const float* s) {
+    if (!shape_ok(out, in, k) || n < 0 || max_batch < 1) return BITSTACK_E_SHAPE;
+    if (!s || (n > 0 && (!sw || !U || !V))) return BITSTACK_E_NULL;
+    for (int j = 0; j < in; ++j)
+        if (!(std::isfinite(s[j]) && s[j] > 0.0f)) return BITSTACK_E_SCALE;
+    return BITSTACK_OK;
+}
+
+int bitstack_pack_image_host(int out, int in, int k, int n, int max_batch,
+                             const uint32_t* sign_words, const uint16_t* U, const uint16_t* V,
+                             const float* s, void* image, size_t image_bytes) {
+    int rc = check_pack_args(out, in, k, n, max_batch, sign_words, U, V, s);
+    if (rc) return rc;
+    if (!image) return BITSTACK_E_NULL;
+    const Geometry g = make_geometry(out, in, n, max_batch);
+    if (image_bytes < g.total) return BITSTACK_E_BUFSIZE;
+    unsigned char* img = static_cast<unsigned char*>(image);
+    std::memset(img, 0, g.total);
+    float* rs = reinterpret_cast<float*>(img + g.off_rs);
+    for (int j = 0; j < in; ++j) rs[j] = 1.0f / s[j];
+    const int wpr = in / 32;
+    for (int i = 0; i < n; ++i) {
+        unsigned char* blk = img + g.off_blocks + size_t(i) * g.block_stride;
+        uint32_t* dsw = reinterpret_cast<uint32_t*>(blk);
+        const uint32_t* csw = sign_words + size_t(i) * out * wpr;
+        for (int o = 0; o < out; ++o)
+            for (int w = 0; w < wpr; ++w) dsw[sign_word_index(in, o, w)] = csw[size_t(o) * wpr + w];
+        uint16_t* dv = reinterpret_cast<uint16_t*>(blk + g.off_v);
+        const uint16_t* cv = V + size_t(i) * in * kRank;
+        for (int j = 0; j < in; ++j)
+            for (int r = 0; r < kRank; ++r) dv[v_index(j, r)] = cv[size_t(j) * kRank + r];
+        std::memcpy(blk + g.off_u, U + size_t(i) * out * kRank, size_t(out) * kRank * 2);
+    }
+    return BITSTACK_OK;
+}
+
+static void unpack_block(const Geometry& g, const unsigned char* blk, uint32_t* sign_words,
+                         uint16_t* U, uint16_t* V) {
+    const int wpr = g.in / 32;
+    if (sign_words) {
+        const uint32_t* dsw = reinterpret_cast<const uint32_t*>(blk);
+        for (int o = 0; o < g.out; ++o)
+            for (int w = 0; w < wpr; ++w)
+                sign_words[size_t(o) * wpr + w] = dsw[sign_word_index(g.in, o, w)];
+    }
+    if (V) {
+        const uint16_t* dv = reinterpret_cast<const uint16_t*>(blk + g.off_v);
+        for (int j = 0; j < g.in; ++j)
+            for (int r = 0; r < kRank; ++r) V[size_t(j) * kRank + r] = dv[v_index(j, r)];
+    }
+    if (U) std::memcpy(U, blk + g.off_u, size_t(g.out) * kRank * 2);
+}
+
+int bitstack_unpack_image_host(int out, int in, int k, int n, int max_batch, const void* image,
+                               int block, uint32_t* sign_words, uint16_t* U, uint16_t* V) {
+    if (!shape_ok(out, in, k) || n < 0 || max_batch < 1) return BITSTACK_E_SHAPE;
+    if (!image) return BITSTACK_E_NULL;
+    if (block < 0 || block >= n) return BITSTACK_E_RANGE;
+    const Geometry g = make_geometry(out, in, n, max_batch);
+    unpack_block(g, static_cast<const unsigned char*>(image) + g.off_blocks + size_t(block) * g.block_stride,
+                 sign_words, U, V);
+    return BITSTACK_OK;
+}
+
+int bitstack_pack_blocks(int out, int in, int k, int n, int max_batch, const uint32_t* sign_words,
+                         const uint16_t* U, const uint16_t* V, const float* s, void* device_buf,
+                         size_t device_buf_bytes, bitstack_stream_t stream,
+                         bitstack_weight_t** handle) {
+    if (!handle) return BITSTACK_E_NULL;
+    *handle = nullptr;
+    int rc = check_pack_args(out, in, k, n, max_batch, sign_words, U, V, s);
+    if (rc) return rc;
+    if (!device_buf) return BITSTACK_E_NULL;
+    if (reinterpret_cast<uintptr_t>(device_buf) % 256) return BITSTACK_E_ALIGN;
+    const Geometry g = make_geometry(out, in, n, max_batch);
+    if (device_buf_bytes < g.total) return BITSTACK_E_BUFSIZE;
+    std::vector<unsigned char> img;
+    try {
+        img.resize(g.total);
+    } catch (const std::bad_alloc&) {
+        return BITSTACK_E_BUFSIZE;
+    }
+    rc = bitstack_pack_image_host(out, in, k, n, max_batch, sign_words, U, V, s, img.data(), img.size());
+    if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    BS_HIP(hipMemcpyAsync(device_buf, img.data(), g.total, hipMemcpyHostToDevice, st));
+    BS_HIP(hipStreamSynchronize(st));
+    bitstack_weight* w = new (std::nothrow) bitstack_weight;
+    if (!w) return BITSTACK_E_BUFSIZE;
+    w->geo = g;
+    w->dev = static_cast<unsigned char*>(device_buf);
+    *handle = w;
+    return BITSTACK_OK;
+}
+
+int bitstack_unpack_blocks(const bitstack_weight_t* w, int block, uint32_t* sign_words, uint16_t* U,
+                           uint16_t* V, bitstack_stream_t stream) {
+    if (!w) return BITSTACK_E_NULL;
+    const Geometry& g = w->geo;
+    if (block < 0 || block >= g.n) return BITSTACK_E_RANGE;
+    std::vector<unsigned char> buf;
+    try {
+        buf.resize(g.block_stride);
+    } catch (const std::bad_alloc&) {
+        return BITSTACK_E_BUFSIZE;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t off = g.off_blocks + size_t(block) * g.block_stride;
+    BS_HIP(hipMemcpyAsync(buf.data(), w->dev + off, g.block_stride, hipMemcpyDeviceToHost, st));
+    BS_HIP(hipStreamSynchronize(st));
+    unpack_block(g, buf.data(), sign_words, U, V);
+    return BITSTACK_OK;
+}
+
+int bitstack_weight_shape(const bitstack_weight_t* w, int* out, int* in, int* k, int* n, int* max_batch) {
+    if (!w) return BITSTACK_E_NULL;
+    if (out) *out = w->geo.out;
+    if (in) *in = w->geo.in;
+    if (k) *k = kRank;
+    if (n) *n = w->geo.n;
+    if (max_batch) *max_batch = w->geo.max_batch;
+    return BITSTACK_OK;
+}
+
+int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w, int n_loaded, void* y,
+                           int y_dtype, int kernel, bitstack_stream_t stream) {
+    if (!x || !w || !y) return BITSTACK_E_NULL;
+    const Geometry& g = w->geo;
+    if (n_loaded < 0 || n_loaded > g.n || batch < 1 || batch > g.max_batch) return BITSTACK_E_RANGE;
+    if (y_dtype != BITSTACK_Y_F16 && y_dtype != BITSTACK_Y_F32) return BITSTACK_E_ARG;
+    if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16) return BITSTACK_E_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    LaunchArgs a;
+    a.x = x;
+    a.y = y;
+    a.image = w->dev;
+    a.geo = g;
+    a.batch = batch;
+    a.n_loaded = n_loaded;
+    a.y_f32 = (y_dtype == BITSTACK_Y_F32);
+    hipError_t e = hipSuccess;
+    if (n_loaded == 0) {
+        e = launch_zero(a, st);
+    } else {
+        if (kernel == BITSTACK_KERNEL_AUTO)
+            kernel = (batch == 1) ? BITSTACK_KERNEL_DECODE : BITSTACK_KERNEL_REFERENCE;
+        switch (kernel) {
+            case BITSTACK_KERNEL_REFERENCE:
+                e = launch_reference(a, st);
+                break;
+            case BITSTACK_KERNEL_DECODE:
+                if (batch != 1) return BITSTACK_E_ARG;
+                e = launch_decode(a, st);
+                break;
+            default:
+                return BITSTACK_E_ARG;
+        }
+    }
+    if (e != hipSuccess) return hip_fail(e);
+    return BITSTACK_OK;
+}
+
+int bitstack_linear_batched(const void* x, int batch, const bitstack_weight_t* w, int n_loaded, void* y,
+                            int y_dtype, bitstack_stream_t stream) {
+    return bitstack_linear_select(x, batch, w, n_loaded, y, y_dtype, BITSTACK_KERNEL_AUTO, stream);
+}
+
+int bitstack_linear(const void* x, const bitstack_weight_t* blocks, int n_loaded, void* y,
+                    bitstack_stream_t stream) {
+    return bitstack_linear_select(x, 1, blocks, n_loaded, y, BITSTACK_Y_F16, BITSTACK_KERNEL_AUTO, stream);
+}
+
+int bitstack_probe_read(const void* device_buf, size_t bytes, void* device_sink, int workgroups,
+                        bitstack_stream_t stream) {
+    if (!device_buf || !device_sink) return BITSTACK_E_NULL;
+    if (reinterpret_cast<uintptr_t>(device_buf) % 16 || bytes % 16) return BITSTACK_E_ALIGN;
+    if (workgroups < 1 || workgroups > (1 << 20)) return BITSTACK_E_RANGE;
+    hipError_t e = launch_stream_read(device_buf, bytes, device_sink, workgroups, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return BITSTACK_OK;
+}
+
+int bitstack_set_option(int option, int value) {
+    if (value < 0) return BITSTACK_E_ARG;
+    switch (option) {
+        case BITSTACK_OPT_DECODE_WAVES: decode_tuning().waves = value; return BITSTACK_OK;
+        case BITSTACK_OPT_DECODE_KSLAB: decode_tuning().kslab = value; return BITSTACK_OK;
+        case 3: decode_tuning().variant = value; return BITSTACK_OK;
+        default: return BITSTACK_E_ARG;
+    }
+}
+
+int bitstack_linear_many(const bitstack_job_t* jobs, int count, int repeat, bitstack_stream_t stream) {
+    if (!jobs) return BITSTACK_E_NULL;
+    if (count < 0 || repeat < 0) return BITSTACK_E_RANGE;
+    for (int r = 0; r < repeat; ++r)
+        for (int i = 0; i < count; ++i) {
+            int rc = bitstack_linear(jobs[i].x, jobs[i].blocks, jobs[i].n_loaded, jobs[i].y, stream);
+            if (rc) return rc;
+        }
+    return BITSTACK_OK;
+}
+
+void bitstack_release(bitstack_weight_t* w) { delete w; }
+
+const char* bitstack_strerror(int code) {
+    switch (code) {
+        case BITSTACK_OK: return "ok";
+        case BITSTACK_E_NULL: return "null pointer argument";
+        case BITSTACK_E_SHAPE: return "unsupported shape (need k == 16, in % 256 == 0, out % 32 == 0)";
+        case BITSTACK_E_RANGE: return "n_loaded, batch or block index out of range";
+        case BITSTACK_E_ALIGN: return "misaligned device pointer";
+        case BITSTACK_E_SCALE: return "scale vector entry not finite or not positive";
+        case BITSTACK_E_BUFSIZE: return "buffer too small";
+        case BITSTACK_E_HIP: return "HIP runtime error (see bitstack_last_hip_error)";
+        case BITSTACK_E_ARG: return "invalid dtype or kernel selector";
+        default: return "unknown error code";
+    }
+}
+
+int bitstack_last_hip_error(void) { return g_last_hip; }
+
+}  // extern "C"

@@ -1,0 +1,32 @@
+// Internal interface between the C-ABI host code and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "layout.h"
+
+namespace bitstack {
+
+struct LaunchArgs {
+    const void* x;         // device fp16 [batch][in]
+    void* y;               // device [batch][out], fp16 or fp32
+    unsigned char* image;  // packed stack (device)
+    Geometry geo;
+    int batch;
+    int n_loaded;
+    bool y_f32;
+};
+
+// Tunables of the decode kernel (0 = choose by shape).
+struct DecodeTuning {
+    int waves;   // wavefronts per workgroup: 4, 8 or 16
+    int kslab;   // columns per workgroup: 512, 1024 or 2048
+    int variant; // experimental code path selector
+};
+DecodeTuning& decode_tuning();
+
+hipError_t launch_stream_read(const void* buf, size_t bytes, void* sink, int blocks, hipStream_t st);
+hipError_t launch_zero(const LaunchArgs& a, hipStream_t st);
+hipError_t launch_reference(const LaunchArgs& a, hipStream_t st);
+hipError_t launch_decode(const LaunchArgs& a, hipStream_t st);
+
+}  // namespace bitstack

@@ -1,0 +1,101 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header
+declares, and its host-side functions (byte accounting, canonical sign packing,
+device-image round trip, argument errors) agree with the oracle and the paper."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2410_23918_amd as B
+from oracle import bitstack_oracle as O
+from workloads import synth as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "bitstack.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(bitstack_[a-z0-9_]+)\s*\(", hdr))
+    assert {"bitstack_linear", "bitstack_pack_blocks", "bitstack_linear_batched"} <= names
+    L = B.lib()
+    for name in sorted(names):
+        assert hasattr(L, name), name
+
+
+def test_block_bytes_matches_eq9_and_oracle():
+    for o, i in [(4096, 4096), (1024, 4096), (14336, 4096), (4096, 14336), (28672, 8192), (512, 512)]:
+        assert B.block_bytes(o, i, 16) == O.block_bytes(o, i, 16)
+    assert B.block_bytes(4096, 4096, 16) == 2359296          # 2.25 MiB, printed in the size table
+    assert B.block_bytes(4096, 4096, 8) == 0                 # only k = 16
+    assert B.block_bytes(4096, 4000, 16) == 0
+    assert B.packed_bytes(4096, 4096, 16, 16, 1) >= 16 * 2359296 + 4096 * 4 + 4096 * 4
+
+
+def test_pack_signs_from_f32_equals_oracle_including_zeros():
+    rng = np.random.default_rng(11)
+    R = rng.standard_normal((33, 96)).astype(np.float32)
+    R[0, :5] = [0.0, -0.0, 1e-38, -1e-38, -0.0]
+    R[rng.random(R.shape) < 0.1] = 0.0
+    got = B.pack_signs_from_f32(R)
+    assert got.dtype == np.uint32
+    assert np.array_equal(got, O.pack_signs(O.sign_pm1(R)))
+
+
+def test_device_image_round_trip_is_bit_exact():
+    rng = W.rng_for(1, 50)
+    out, inn, n = 96, 768, 3
+    s = W.column_scales(rng, inn)
+    S, U, V = W.synthetic_blocks(rng, out, inn, n, 16, s, 0.02)
+    sw = np.stack([O.pack_signs(S[i]) for i in range(n)])
+    img = B.pack_image_host(sw, U, V, s, max_batch=4)
+    assert img.nbytes == B.packed_bytes(out, inn, 16, n, 4)
+    for b in range(n):
+        sw2, U2, V2 = B.unpack_image_host(img, out, inn, 16, n, 4, b)
+        assert np.array_equal(sw2, sw[b])
+        assert np.array_equal(U2.view(np.uint16), U[b].view(np.uint16))
+        assert np.array_equal(V2.view(np.uint16), V[b].view(np.uint16))
+    # each block is one contiguous range of exactly Eq. 9's byte count, and the
+    # image stores 1/s in front
+    assert np.allclose(img[: inn * 4].view(np.float32), 1.0 / s, rtol=1e-7)
+    # changing one sign bit changes exactly one bit of the image
+    sw3 = sw.copy(); sw3[1, 40, 7] ^= np.uint32(1 << 13)
+    img3 = B.pack_image_host(sw3, U, V, s, max_batch=4)
+    diff = np.bitwise_xor(img, img3)
+    assert int(np.unpackbits(diff).sum()) == 1
+    first = int(np.nonzero(diff)[0][0])
+    blk0 = (inn * 4 + 255) // 256 * 256
+    assert blk0 + B.block_bytes(out, inn) <= first < blk0 + 2 * B.block_bytes(out, inn)
+
+
+def test_error_codes_on_the_host():
+    L = B.lib()
+    rng = W.rng_for(1, 51)
+    out, inn, n = 32, 256, 1
+    s = W.column_scales(rng, inn)
+    S, U, V = W.synthetic_blocks(rng, out, inn, n, 16, s, 0.02)
+    sw = np.stack([O.pack_signs(S[0])])
+    with pytest.raises(B.BitStackError) as e:
+        bad = s.copy(); bad[3] = 0.0
+        B.pack_image_host(sw, U, V, bad)
+    assert e.value.code == -5
+    with pytest.raises(B.BitStackError) as e:
+        bad = s.copy(); bad[3] = np.inf
+        B.pack_image_host(sw, U, V, bad)
+    assert e.value.code == -5
+    img = B.pack_image_host(sw, U, V, s)
+    with pytest.raises(B.BitStackError) as e:
+        B.unpack_image_host(img, out, inn, 16, n, 1, 1)
+    assert e.value.code == -3
+    # too-small buffer, null pointers, bad shapes, unknown option
+    small = np.empty(16, np.uint8)
+    p = lambda a: a.ctypes.data_as(C.c_void_p)
+    assert L.bitstack_pack_image_host(out, inn, 16, n, 1, p(sw), p(U), p(V), p(s), p(small), 16) == -6
+    assert L.bitstack_pack_image_host(out, inn, 16, n, 1, None, p(U), p(V), p(s), p(img), img.nbytes) == -1
+    assert L.bitstack_pack_image_host(out, 100, 16, n, 1, p(sw), p(U), p(V), p(s), p(img), img.nbytes) == -2
+    assert L.bitstack_linear(None, None, 0, None, None) == -1
+    assert L.bitstack_set_option(99, 1) == -8
+    assert B.strerror(-5).startswith("scale")
+    assert B.strerror(0) == "ok"

@@ -1,0 +1,196 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded
+inputs.  Tolerance: max_o |y - y_ref| / max_o |y_ref| <= 2e-3 per token (fp16 in,
+fp32 accumulate, fp16 out); sign packing and the device-layout round trip bit-exact."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from oracle import bitstack_oracle as O
+from workloads import synth as W
+
+from _cases import acts, synth_stack, true_stack
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2410_23918_amd as B
+    B.lib()
+    return B
+
+
+def _to_dev(x):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+
+
+def _run(B, ps, x, n_loaded, kernel, dtype="f16"):
+    import torch
+    xd = _to_dev(x)
+    dt = torch.float16 if dtype == "f16" else torch.float32
+    y = ps.linear_batched(xd, n_loaded, out_dtype=dt, kernel=kernel)
+    torch.cuda.synchronize()
+    return y.float().cpu().numpy().astype(np.float64)
+
+
+def _pack(B, st, max_batch=1):
+    return B.PackedStack(st.sign_words(), st.U, st.V, st.s, max_batch=max_batch)
+
+
+# ------------------------------------------------------------------ config 1
+def test_cfg1_all_prefixes_both_kernels(B):
+    st = true_stack(1, 512, 512, 4)
+    ps = _pack(B, st)
+    x = acts(1, 1, 512)
+    for nl in range(5):
+        ref = O.forward_dense(st, x, nl)
+        for kern in (B.KERNEL_REFERENCE, B.KERNEL_DECODE):
+            for dt in ("f16", "f32"):
+                y = _run(B, ps, x, nl, kern, dt)
+                if nl == 0:
+                    assert not y.any()
+                else:
+                    err = O.relative_error(y, ref)
+                    print(f"cfg1 n_loaded={nl} kernel={kern} {dt}: rel err {err:.2e}", flush=True)
+                    assert err <= TOL
+    # dense and factored oracle forms agree on the same inputs (config 1's own check)
+    assert O.relative_error(O.forward_factored(st, x, 4), O.forward_dense(st, x, 4)) < 1e-12
+
+
+def test_cfg1_packing_is_bit_exact(B):
+    st = true_stack(1, 512, 512, 4)
+    # library's canonical sign packing of the float residuals == oracle's
+    rng = W.rng_for(1, 0)
+    Wt = W.dense_weight(rng, 512, 512, 0.02, False)
+    s = W.column_scales(rng, 512)
+    R = Wt.astype(np.float64) * s[None, :]
+    sw = st.sign_words()
+    for i in range(4):
+        assert np.array_equal(B.pack_signs_from_f32(R.astype(np.float32)), O.pack_signs(O.sign_pm1(R.astype(np.float32))))
+        assert np.array_equal(O.pack_signs(O.sign_pm1(R)), sw[i])
+        R = R - O.block_dense(st.S[i], st.U[i], st.V[i])
+    ps = _pack(B, st)
+    for i in range(4):
+        sw2, U2, V2 = ps.unpack_block(i)
+        assert np.array_equal(sw2, sw[i])
+        assert np.array_equal(U2.view(np.uint16), st.U[i].view(np.uint16))
+        assert np.array_equal(V2.view(np.uint16), st.V[i].view(np.uint16))
+
+
+def test_repeat_calls_leave_workspace_clean(B):
+    st = true_stack(1, 512, 512, 4)
+    ps = _pack(B, st)
+    x = acts(1, 1, 512)
+    ref = O.forward_dense(st, x, 4)
+    for it in range(5):
+        nl = [4, 2, 4, 0, 4][it]
+        y = _run(B, ps, x, nl, B.KERNEL_DECODE)
+        want = O.forward_dense(st, x, nl)
+        if nl:
+            assert O.relative_error(y, want) <= TOL
+        else:
+            assert not y.any()
+
+
+# ------------------------------------------------------------------ edge shapes
+@pytest.mark.parametrize("out,inn,n", [(32, 256, 1), (96, 768, 3), (160, 1024, 2), (1056, 512, 2),
+                                       (192, 1536, 2), (64, 2048, 2), (2080, 2048, 1)])
+def test_small_and_ragged_shapes(B, out, inn, n):
+    st = synth_stack(3, out, inn, n)
+    ps = _pack(B, st, max_batch=3)
+    x = acts(3, 3, inn)
+    ref = O.forward_dense(st, x, n)
+    y = _run(B, ps, x, n, B.KERNEL_REFERENCE)
+    assert O.relative_error(y, ref) <= TOL
+    min_slab = 1024 if inn % 1024 == 0 else 512 if inn % 512 == 0 else 256
+    for waves in (4, 8, 16):
+        for ks in (256, 512, 1024, 2048):
+            if inn % ks or ks < min_slab or (ks == 256 and waves != 4) or (ks == 2048 and waves == 16):
+                continue
+            B.set_option(B.OPT_DECODE_WAVES, waves); B.set_option(B.OPT_DECODE_KSLAB, ks)
+            try:
+                y1 = _run(B, ps, x[:1], n, B.KERNEL_DECODE)
+            finally:
+                B.set_option(B.OPT_DECODE_WAVES, 0); B.set_option(B.OPT_DECODE_KSLAB, 0)
+            err = O.relative_error(y1, ref[:1])
+            print(f"{out}x{inn} waves={waves} ks={ks}: {err:.2e}", flush=True)
+            assert err <= TOL
+
+
+def test_argument_errors_on_device(B):
+    import torch
+    st = synth_stack(3, 32, 256, 1)
+    ps = _pack(B, st, max_batch=2)
+    L = B.lib()
+    x = torch.zeros(2 * 256 + 8, dtype=torch.float16, device="cuda:0")
+    y = torch.zeros(2 * 32 + 8, dtype=torch.float16, device="cuda:0")
+    s0 = C.c_void_p(0)
+    assert L.bitstack_linear(x.data_ptr(), ps.handle, 2, y.data_ptr(), s0) == -3      # n_loaded > n
+    assert L.bitstack_linear(x.data_ptr(), ps.handle, -1, y.data_ptr(), s0) == -3
+    assert L.bitstack_linear(x.data_ptr() + 2, ps.handle, 1, y.data_ptr(), s0) == -4  # misaligned
+    assert L.bitstack_linear_batched(x.data_ptr(), 3, ps.handle, 1, y.data_ptr(), 0, s0) == -3  # batch > max
+    assert L.bitstack_linear_batched(x.data_ptr(), 1, ps.handle, 1, y.data_ptr(), 7, s0) == -8
+    assert L.bitstack_linear_select(x.data_ptr(), 2, ps.handle, 1, y.data_ptr(), 0, B.KERNEL_DECODE, s0) == -8
+    assert L.bitstack_unpack_blocks(ps.handle, 5, None, None, None, s0) == -3
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ config 2
+def test_cfg2_llama_attn_proj_true_iavd(B):
+    st = true_stack(2, 4096, 4096, 16, method="subspace", iters=8)
+    ps = _pack(B, st)
+    x = acts(2, 1, 4096)
+    for nl in (16, 7, 1):
+        ref = O.forward_dense(st, x, nl)
+        for kern in (B.KERNEL_DECODE, B.KERNEL_REFERENCE):
+            y = _run(B, ps, x, nl, kern)
+            err = O.relative_error(y, ref)
+            print(f"cfg2 n_loaded={nl} kernel={kern}: rel err {err:.2e}", flush=True)
+            assert err <= TOL
+    sw2, U2, V2 = ps.unpack_block(15)
+    assert np.array_equal(sw2, st.sign_words()[15])
+
+
+# ------------------------------------------------------------------ config 3
+@pytest.mark.parametrize("out,inn", [(14336, 4096), (4096, 14336)])
+def test_cfg3_llama_mlp_batches(B, out, inn):
+    st = synth_stack(3, out, inn, 16)
+    ps = _pack(B, st, max_batch=16)
+    x = acts(3, 16, inn)
+    ref = O.forward_dense(st, x, 16)
+    y = _run(B, ps, x[:1], 16, B.KERNEL_DECODE)
+    err = O.relative_error(y, ref[:1])
+    print(f"cfg3 {out}x{inn} B=1 decode: {err:.2e}", flush=True)
+    assert err <= TOL
+    for b in (1, 4, 16):
+        y = _run(B, ps, x[:b], 16, B.KERNEL_AUTO)
+        err = O.relative_error(y, ref[:b])
+        print(f"cfg3 {out}x{inn} B={b} auto: {err:.2e}", flush=True)
+        assert err <= TOL
+
+
+# ------------------------------------------------------------------ config 4
+def test_cfg4_decoder_layer_variable_stack_heights(B):
+    rng = W.rng_for(4, 0)
+    nl_all = W.variable_n_loaded(rng, 32 * 7)
+    assert nl_all.min() >= 8 and nl_all.max() <= 24
+    rows_rng = W.rng_for(4, 1)
+    for m, (name, out, inn) in enumerate(W.llama3_8b_layer_shapes()):
+        nl = int(nl_all[m])
+        st = synth_stack(4, out, inn, nl, tag=m)   # blocks past n_loaded are never read
+        ps = _pack(B, st)
+        x = acts(4, 1, inn, tag=m)
+        rows = np.sort(rows_rng.choice(out, size=256, replace=False))
+        ref = O.forward_rows(st, x, nl, rows)
+        y = _run(B, ps, x, nl, B.KERNEL_AUTO)
+        # sampled rows; scale by the max over the sample
+        err = O.relative_error(y[:, rows], ref)
+        print(f"cfg4 {name} {out}x{inn} n_loaded={nl}: {err:.2e}", flush=True)
+        assert err <= TOL
+        del ps
+    synth_stack.cache_clear()
