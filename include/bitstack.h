@@ -159,8 +159,9 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* bl
  * the built-in choice.  Unknown options or unsupported values give BITSTACK_E_ARG
  * (at the next launch for values). */
 enum {
-    BITSTACK_OPT_DECODE_WAVES = 1, /* wavefronts per workgroup of the decode kernel: 4, 8, 16 */
-    BITSTACK_OPT_DECODE_KSLAB = 2  /* input columns per workgroup: 256, 512, 1024, 2048      */
+    BITSTACK_OPT_DECODE_KSLAB = 2, /* input columns per workgroup of the decode kernel: 256, 512, 1024 */
+    BITSTACK_OPT_DECODE_BGROUPS = 3 /* workgroups sharing one (row slab, column slab) pair; each
+                                       walks every BGROUPS-th block of the loaded prefix      */
 };
 int bitstack_set_option(int option, int value);
 

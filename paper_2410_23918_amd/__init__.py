@@ -7,7 +7,7 @@ from .binding import (  # noqa: F401
     BitStackError,
     PackedStack,
     KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL,
-    OPT_DECODE_WAVES, OPT_DECODE_KSLAB,
+    OPT_DECODE_KSLAB, OPT_DECODE_BGROUPS,
     block_bytes,
     lib,
     linear_many,

@@ -12,7 +12,7 @@ _lib = None
 
 KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL = 0, 1, 2, 3
 Y_F16, Y_F32 = 0, 1
-OPT_DECODE_WAVES, OPT_DECODE_KSLAB = 1, 2
+OPT_DECODE_KSLAB, OPT_DECODE_BGROUPS = 2, 3
 
 
 class BitStackError(RuntimeError):

@@ -92,6 +92,17 @@ int bitstack_pack_image_host(int out, int in, int k, int n, int max_batch,
         for (int j = 0; j < in; ++j)
             for (int r = 0; r < kRank; ++r) dv[v_index(j, r)] = cv[size_t(j) * kRank + r];
         std::memcpy(blk + g.off_u, U + size_t(i) * out * kRank, size_t(out) * kRank * 2);
+        // derived: max_r |V[j][r]| per channel (fp16 magnitudes compare like their bit patterns)
+        uint16_t* vm = reinterpret_cast<uint16_t*>(img + g.off_vmax) + size_t(i) * in;
+        for (int j = 0; j < in; ++j) {
+            uint16_t m = 0;
+            for (int r = 0; r < kRank; ++r) {
+                uint16_t a = cv[size_t(j) * kRank + r] & 0x7FFFu;
+                if (a > 0x7C00u) a = 0x7C00u;  // NaN payloads: treat as infinity
+                if (a > m) m = a;
+            }
+            vm[panel_index(j)] = m;
+        }
     }
     return BITSTACK_OK;
 }
@@ -245,9 +256,8 @@ int bitstack_probe_read(const void* device_buf, size_t bytes, void* device_sink,
 int bitstack_set_option(int option, int value) {
     if (value < 0) return BITSTACK_E_ARG;
     switch (option) {
-        case BITSTACK_OPT_DECODE_WAVES: decode_tuning().waves = value; return BITSTACK_OK;
         case BITSTACK_OPT_DECODE_KSLAB: decode_tuning().kslab = value; return BITSTACK_OK;
-        case 3: decode_tuning().variant = value; return BITSTACK_OK;
+        case BITSTACK_OPT_DECODE_BGROUPS: decode_tuning().bgroups = value; return BITSTACK_OK;
         default: return BITSTACK_E_ARG;
     }
 }

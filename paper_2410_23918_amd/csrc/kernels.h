@@ -18,9 +18,8 @@ struct LaunchArgs {
 
 // Tunables of the decode kernel (0 = choose by shape).
 struct DecodeTuning {
-    int waves;   // wavefronts per workgroup: 4, 8 or 16
-    int kslab;   // columns per workgroup: 512, 1024 or 2048
-    int variant; // experimental code path selector
+    int kslab;   // columns per workgroup: 256, 512 or 1024
+    int bgroups; // block groups (workgroups per row/column slab pair)
 };
 DecodeTuning& decode_tuning();
 

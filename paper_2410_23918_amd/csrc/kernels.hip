@@ -15,9 +15,9 @@
 //     against the slab's exact max |T|, pre-shifted by 2^-(3 - t%4) so that all
 //     column classes of a nibble land on one scale, and split into a high and a
 //     low signed byte: 16 ranks x {hi, lo} = the 32 rows of the A operand.
-//   * accumulation is exact int32; two accumulator sets (low-nibble and
-//     high-nibble classes) are merged by shifts in the epilogue; S = 2B - 1 is
-//     undone with the exact integer column sums of the panel.
+//   * accumulation is exact int32 (the high-nibble classes are brought down with
+//     one shift of the sign words, so a single accumulator set serves all eight
+//     classes); S = 2B - 1 is undone with the exact integer column sums of the panel.
 // Work is split over (block, column slab, row slab) workgroups.  Each writes its
 // fp32 partial sums to its own workspace row; the last workgroup to arrive for a
 // row slab (one agent-scope counter per slab) adds the rows up in a fixed order,
@@ -26,6 +26,8 @@
 // whole sign stream, and a fence per thread slower still.)
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "kernels.h"
 #include "layout.h"
@@ -40,6 +42,15 @@ typedef short v2s __attribute__((ext_vector_type(2)));
 // Development aid (off in the shipped build): wave 0 of every workgroup stamps the
 // constant-rate clock at phase boundaries.
 __device__ unsigned long long g_trace[8192 * 8];
+#define BS_TRACE2(role, i)                                                            \
+    do {                                                                             \
+        if (lane == 0 && (wave == 0 || wave == kConsumers) && blockIdx.x < 1024 && (i) < 24) \
+            g_trace2[(blockIdx.x * 2 + (role)) * 24 + (i)] = wall_clock64();          \
+    } while (0)
+__device__ unsigned long long g_trace2[1024 * 2 * 24];
+extern "C" int bitstack_debug_trace2(unsigned long long* host, int n) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace2), size_t(n) * 8);
+}
 #define BS_TRACE(i)                                                                  \
     do {                                                                             \
         if (tid == 0 && blockIdx.x < 8192) g_trace[blockIdx.x * 8 + (i)] = wall_clock64(); \
@@ -49,10 +60,11 @@ extern "C" int bitstack_debug_trace(unsigned long long* host, int n) {
 }
 #else
 #define BS_TRACE(i) do { } while (0)
+#define BS_TRACE2(role, i) do { } while (0)
 #endif
 
 DecodeTuning& decode_tuning() {
-    static DecodeTuning t = {0, 0, 0};
+    static DecodeTuning t = {0, 0};
     return t;
 }
 
@@ -62,7 +74,11 @@ struct KParams {
     const float* rs;      // [in]   1/s
     const unsigned char* blocks;
     size_t block_stride, off_v, off_u;
+    const __half* vmax;   // [n][in] max_r |V[j][r]|, panel order
     float* part;          // [part_slots][out] partial sums
+    int part_slots;
+    unsigned sign_bytes_total;  // n * block_stride: extent of the buffer descriptor over the blocks
+    int n_bg;             // block groups: a workgroup walks blocks bg, bg + n_bg, ...
     unsigned* ctr;        // arrival counters (zero between calls)
     int out, in, batch, n_loaded;
     int n_rs, n_ks;       // row slabs, column slabs per block
@@ -78,7 +94,10 @@ static KParams make_params(const LaunchArgs& a) {
     p.block_stride = a.geo.block_stride;
     p.off_v = a.geo.off_v;
     p.off_u = a.geo.off_u;
+    p.vmax = reinterpret_cast<const __half*>(a.image + a.geo.off_vmax);
     p.part = reinterpret_cast<float*>(a.image + a.geo.off_part);
+    p.part_slots = a.geo.part_slots;
+    p.n_bg = 1;
     p.ctr = reinterpret_cast<unsigned*>(a.image + a.geo.off_ctr);
     p.out = a.geo.out;
     p.in = a.geo.in;
@@ -195,30 +214,57 @@ hipError_t launch_reference(const LaunchArgs& a, hipStream_t st) {
 
 // ---------------------------------------------------------------- decode kernel
 constexpr float kQMax = 32512.0f;  // |q| <= 127*256: the high byte stays in int8 after +128 rounding
+constexpr int kMaxBlocksPerWg = 32;
+constexpr int kConsumers = 8;      // wavefronts that stream signs through the matrix cores
+constexpr int kProducers = 4;      // wavefronts that build the panel fragments
+constexpr int kTilesPerWave = 4;   // 32-row tiles per consumer wavefront
+constexpr int kDecodeRows = kConsumers * kTilesPerWave * kTileRows;   // rows per workgroup (1024)
 
 __device__ __forceinline__ float wave_max(float v) {
     for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
     return v;
 }
 
-template <int WAVES, int KS, int WIN, int OCC, bool EARLY>
-__global__ __launch_bounds__(WAVES * 64, OCC) void k_decode(KParams p) {
-    constexpr int NT = WAVES * 64;
+// One workgroup owns a row slab (1024 rows) and a column slab (KS columns) and walks
+// through every n_bg-th block of the loaded prefix, keeping its fp32 results in
+// registers.  The twelve wavefronts are specialised:
+//   * producers (4, one per SIMD) build, for the next block, the int8 panel
+//     fragments of the slab in LDS (double buffered), the integer column sums and a
+//     copy of the U rows;
+//   * consumers (8, two per SIMD) own 128 rows each.  Their only global loads are the
+//     sign units, issued unconditionally (buffer loads whose out-of-range lanes
+//     return zero without touching memory) one block ahead into a register window,
+//     so the in-order memory counter never makes them wait for anything younger
+//     than the unit they need: 16 KiB per wavefront, 128 KiB per compute unit in
+//     flight, which is what the HBM pipe needs to stay full.  Per unit: 8 masks x
+//     (4 ANDs + 1 matrix-core instruction).  Per block: a short epilogue folds the
+//     int32 accumulators into running fp32 sums using U, scale and column sums from
+//     LDS.
+// One barrier per block separates "fragments of block q+1 written" from "fragments of
+// block q read".
+template <int KS>
+__global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KParams p) {
     constexpr int NCH = KS / kChunkCols;   // sign chunks per slab
-    constexpr int R = 2;                   // 32-row tiles per wavefront
-    constexpr int RS = WAVES * R * kTileRows;
-    constexpr int G = (KS + NT - 1) / NT;  // 16-value panel groups per thread (KS groups per slab)
-    constexpr int XPT = (KS + NT - 1) / NT;  // activation values per thread
-    constexpr int WCH = (WIN < NCH ? WIN : NCH);  // chunks of sign data in flight per tile
+    constexpr int R = kTilesPerWave;       // 32-row tiles per consumer wavefront
+    constexpr int RS = kDecodeRows;
+    constexpr int PT = kProducers * 64;    // producer threads
+    constexpr int NT = (kConsumers + kProducers) * 64;
+    constexpr int G = KS / PT;             // 16-value panel groups per producer thread
+    static_assert(KS % PT == 0 && G >= 1, "slab must give every producer thread whole groups");
+    constexpr int FRAG_BYTES = KS * 32;
+    constexpr int U_BYTES = RS * 32;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    v4i* frag = reinterpret_cast<v4i*>(smem);                         // [NCH*8][64] x 16 B
-    float* xs = reinterpret_cast<float*>(smem + size_t(KS) * 32);     // [KS]
-    int* cs = reinterpret_cast<int*>(smem + size_t(KS) * 36);         // [2][16]
-    float* red = reinterpret_cast<float*>(smem + size_t(KS) * 36 + 128);  // [WAVES]
-    unsigned* flag = reinterpret_cast<unsigned*>(smem + size_t(KS) * 36 + 128 + 64);
+    v4i* frag0 = reinterpret_cast<v4i*>(smem);                                   // [2][NCH*8][64] x 16 B
+    uint4* ulds = reinterpret_cast<uint4*>(smem + 2 * FRAG_BYTES);               // [2][RS][2] x 16 B
+    float* xs = reinterpret_cast<float*>(smem + 2 * FRAG_BYTES + 2 * U_BYTES);   // [KS]
+    float* amax_w = xs + KS;                                                     // [kProducers][kMaxBlocksPerWg]
+    int* cs = reinterpret_cast<int*>(amax_w + kProducers * kMaxBlocksPerWg);     // [3][32]
+    unsigned* flag = reinterpret_cast<unsigned*>(cs + 96);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool producer = wave >= kConsumers;
+    const int ptid = tid - kConsumers * 64;   // producer thread index (valid when producer)
 
     // workgroup id -> work item, contiguous ranges of items per XCD (ids are dealt
     // round-robin to the 8 XCDs), so that the workgroups sharing a V slab share an L2
@@ -228,123 +274,113 @@ __global__ __launch_bounds__(WAVES * 64, OCC) void k_decode(KParams p) {
     const unsigned item = xcd * q8 + min(xcd, rem) + slot;
     const int rs_i = item % p.n_rs;
     const int ks_i = (item / p.n_rs) % p.n_ks;
-    const int blk_i = item / (p.n_rs * p.n_ks);
-    const int slot_i = blk_i * p.n_ks + ks_i;   // this workgroup's partial-sum row
+    const int bg_i = item / (p.n_rs * p.n_ks);
+    const int slot_i = bg_i * p.n_ks + ks_i;   // this workgroup's partial-sum row
+    const int nb = (p.n_loaded - bg_i + p.n_bg - 1) / p.n_bg;   // blocks bg_i, bg_i + n_bg, ...
 
-    const unsigned char* blk = p.blocks + size_t(blk_i) * p.block_stride;
     const int nch_total = p.in / kChunkCols;
     const int c0 = ks_i * NCH;               // first chunk of this slab
     const int k0 = c0 * kChunkCols;
     const int n_rt = p.out / kTileRows;
-    const int rt_base = rs_i * (WAVES * R) + wave * R;
+    const int row0 = rs_i * RS;
+    auto block_index = [&](int q) { return bg_i + q * p.n_bg; };
+    auto block_ptr = [&](int q) { return p.blocks + size_t(block_index(q)) * p.block_stride; };
+
+    auto amax_of = [&](int q) {
+        float a = amax_w[q];
+#pragma unroll
+        for (int w = 1; w < kProducers; ++w) a = fmaxf(a, amax_w[w * kMaxBlocksPerWg + q]);
+        return a;
+    };
 
     BS_TRACE(0);
-    // ---- every global load the prologue needs goes out first, in the order it is
-    // consumed: activations and scales, the V slab, then the head of the sign stream
-    float xv[XPT], rv[XPT];
+    // Both roles pass the same barriers: P1 (x/s slab in LDS), P2 (per-block maxima in
+    // LDS), P3 (block 0 staged), then one per block.
+    if (producer) {
+        // ============================================================== producers
+        // one producer wave shares a SIMD with two consumer waves that are almost never
+        // stalled; without a raised issue priority it only gets their leftovers
+        __builtin_amdgcn_s_setprio(2);
+        constexpr int PER = U_BYTES / 16 / PT;   // 16-byte pieces of U per producer thread
+        constexpr int XP = KS / PT;              // consecutive panel positions per producer thread
+        // Raw V slab and U rows of a block are fetched one stage ahead (always issued, for
+        // a block index clamped to the last one, so that the in-order memory counter lets
+        // the older set be consumed while the younger one is still in flight).
+        struct Raw {
+            uint4 v[G][2];
+        };
+        struct URows {
+            uint4 u[PER];
+        };
+        // Thread ptid stages G consecutive 16-value groups: panel position (ptid*G)/16
+        // (one 32-column operand of one class) and the ranks rk0 .. rk0+G-1.
+        static_assert(G == 4 || G == 2 || G == 1, "group mapping");
+        auto load_raw = [&](int q) -> Raw {
+            Raw raw;
+            const unsigned char* blk = block_ptr(max(min(q, nb - 1), 0));
+            const uint4* vsl = reinterpret_cast<const uint4*>(blk + p.off_v) + size_t(c0) * 256 * 2 +
+                               size_t(ptid) * G * 2;
 #pragma unroll
-    for (int m = 0; m < XPT; ++m) {
-        const int idx = tid + m * NT;
-        xv[m] = rv[m] = 0.0f;
-        if (idx < KS) {
-            const int e = idx & 15, g = (idx >> 4) & 1, t = (idx >> 5) & 7, c = idx >> 8;
-            const int col = k0 + panel_col(c, t, g, e);
-            xv[m] = __half2float(p.x[col]);
-            rv[m] = p.rs[col];
-        }
-    }
-    uint4 vraw[G][2];
-    const uint4* vsl = reinterpret_cast<const uint4*>(blk + p.off_v) + size_t(c0) * 256 * 2;
-#pragma unroll
-    for (int m = 0; m < G; ++m) {
-        const int gidx = tid + m * NT;
-        vraw[m][0] = vraw[m][1] = uint4{0, 0, 0, 0};
-        if (gidx < KS) {
-            vraw[m][0] = vsl[size_t(gidx) * 2];
-            vraw[m][1] = vsl[size_t(gidx) * 2 + 1];
-        }
-    }
-    const v4i* sgn = reinterpret_cast<const v4i*>(blk);
-    const v4i* srow[R];
-    bool live[R];
-    v4i win[WCH][R];
-#pragma unroll
-    for (int tl = 0; tl < R; ++tl) {
-        live[tl] = rt_base + tl < n_rt;
-        srow[tl] = sgn + (size_t(live[tl] ? rt_base + tl : 0) * nch_total + c0) * 64 + lane;
-#pragma unroll
-        for (int c = 0; c < WCH; ++c) {
-            win[c][tl] = v4i{0, 0, 0, 0};
-            if (EARLY && live[tl]) win[c][tl] = srow[tl][size_t(c) * 64];
-        }
-    }
-
-    // ---- activation slab x/s in panel order
-    if (tid < 32) cs[tid] = 0;
-#pragma unroll
-    for (int m = 0; m < XPT; ++m) {
-        const int idx = tid + m * NT;
-        if (idx < KS) xs[idx] = xv[m] * rv[m];
-    }
-    __syncthreads();
-    BS_TRACE(1);
-    if (!EARLY) {   // sign stream starts once the prologue's own loads are home
-#pragma unroll
-        for (int tl = 0; tl < R; ++tl)
-#pragma unroll
-            for (int c = 0; c < WCH; ++c)
-                if (live[tl]) win[c][tl] = srow[tl][size_t(c) * 64];
-    }
-
-    // ---- panel T = V * x/s for this slab, kept in registers; exact max |T|
-    float T[G][16];
-    float amax = 0.0f;
-#pragma unroll
-    for (int m = 0; m < G; ++m) {
-        const int gidx = tid + m * NT;
-        if (gidx < KS) {
-            const uint4 va = vraw[m][0], vb = vraw[m][1];
-            const unsigned vw[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
-            const float* xg = xs + (gidx >> 4) * 16;
-#pragma unroll
-            for (int e2 = 0; e2 < 8; ++e2) {
-                const __half2 h = *reinterpret_cast<const __half2*>(&vw[e2]);
-                T[m][2 * e2] = __low2float(h) * xg[2 * e2];
-                T[m][2 * e2 + 1] = __high2float(h) * xg[2 * e2 + 1];
-                amax = fmaxf(amax, fmaxf(fabsf(T[m][2 * e2]), fabsf(T[m][2 * e2 + 1])));
+            for (int m = 0; m < G; ++m) {
+                raw.v[m][0] = vsl[m * 2];
+                raw.v[m][1] = vsl[m * 2 + 1];
             }
-        }
-    }
-    amax = wave_max(amax);
-    if (lane == 0) red[wave] = amax;
-    __syncthreads();
-    BS_TRACE(2);
-    amax = red[0];
+            // keep these loads where they are: scheduled below the code that consumes the
+            // older set, the consumer of that set would have to drain them as well
+            __builtin_amdgcn_sched_barrier(0);
+            return raw;
+        };
+        auto load_u = [&](int q) -> URows {
+            URows ur;
+            const unsigned char* blk = block_ptr(max(min(q, nb - 1), 0));
+            // rows past the end of the matrix: re-read the last valid piece (never used for output)
+            const uint4* usrc = reinterpret_cast<const uint4*>(blk + p.off_u);
+            const int last_piece = p.out * 2 - 1;
 #pragma unroll
-    for (int w = 1; w < WAVES; ++w) amax = fmaxf(amax, red[w]);
-    const float inv = amax > 0.0f ? (kQMax / 32767.0f) / amax : 0.0f;
-
-    // ---- quantise, split into bytes, write A-operand fragments, integer column sums
-    {
-        int csH = 0, csL = 0;
+            for (int k = 0; k < PER; ++k) ur.u[k] = usrc[min(row0 * 2 + ptid + k * PT, last_piece)];
+            __builtin_amdgcn_sched_barrier(0);
+            return ur;
+        };
+        auto store_u = [&](int q, const URows ur) {
+            uint4* udst = ulds + (q & 1) * (U_BYTES / 16);
 #pragma unroll
-        for (int m = 0; m < G; ++m) {
-            const int gidx = tid + m * NT;
-            if (gidx < KS) {
-                const int r = gidx & 15, pos = gidx >> 4;
-                const int g = pos & 1, t = (pos >> 1) & 7, c = pos >> 4;
-                const int tc = t & 3;
-                // sign byte of class t is 2^(t%4) (times 16 in the high nibble): pre-dividing
-                // by it puts every class on one scale, (sign byte) * q = 32512 * T / amax
-                float f = inv * (tc == 0 ? 1.0f : tc == 1 ? 0.5f : tc == 2 ? 0.25f : 0.125f);
-                if (t == 7) f = -f;                      // byte 0x80 is -128
-                const int gamma = (t == 7) ? -8 : (1 << tc);
+            for (int k = 0; k < PER; ++k) udst[ptid + k * PT] = ur.u[k];
+        };
+        // quantise block q's slab of the panel from raw V into fragment buffer (q & 1)
+        auto quantise = [&](int q, const Raw raw) {
+            v4i* frag = frag0 + (q & 1) * (FRAG_BYTES / 16);
+            int* csq = cs + (q % 3) * 32;
+            const float amax = amax_of(q);
+            const float inv = amax > 0.0f ? (kQMax / 32767.0f) / amax : 0.0f;
+            const int gbase = ptid * G;            // first group of this thread
+            const int pos = gbase >> 4, rk0 = gbase & 15;
+            const int g = pos & 1, t = (pos >> 1) & 7, c = pos >> 4;
+            // the sign byte of class t is 2^(t%4) (high-nibble classes are shifted down by
+            // the consumers): pre-dividing by it puts every class on one scale,
+            // (sign byte) * q = 32512 * T / amax
+            const int tc = t & 3;
+            const float f = inv * __int_as_float((127 - tc) << 23);   // inv * 2^-tc
+            float xf[16];
+            {
+                const float4* xg = reinterpret_cast<const float4*>(xs + pos * 16);
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const float4 v = xg[k];
+                    xf[4 * k] = v.x * f; xf[4 * k + 1] = v.y * f; xf[4 * k + 2] = v.z * f; xf[4 * k + 3] = v.w * f;
+                }
+            }
+            int sums[G][2];
+#pragma unroll
+            for (int m = 0; m < G; ++m) {
+                const uint4 va = raw.v[m][0], vb = raw.v[m][1];
+                const unsigned vw[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
                 unsigned qq[8];
 #pragma unroll
                 for (int e2 = 0; e2 < 8; ++e2) {
-                    v2s q = __builtin_amdgcn_cvt_pknorm_i16(T[m][2 * e2] * f, T[m][2 * e2 + 1] * f);
-                    q += v2s{128, 128};  // high byte becomes round(q / 256), low byte q ^ 0x80
-                    qq[e2] = *reinterpret_cast<unsigned*>(&q);
+                    const __half2 h = *reinterpret_cast<const __half2*>(&vw[e2]);
+                    v2s qv = __builtin_amdgcn_cvt_pknorm_i16(__low2float(h) * xf[2 * e2], __high2float(h) * xf[2 * e2 + 1]);
+                    qv += v2s{128, 128};  // high byte becomes round(q / 256), low byte q ^ 0x80
+                    qq[e2] = *reinterpret_cast<unsigned*>(&qv);
                 }
                 v4i H, L;
                 int sH = 0, sL = 0;
@@ -357,126 +393,280 @@ __global__ __launch_bounds__(WAVES * 64, OCC) void k_decode(KParams p) {
                     sH = __builtin_amdgcn_sdot4(int(hi), 0x01010101, sH, false);
                     sL = __builtin_amdgcn_sdot4(int(lo), 0x01010101, sL, false);
                 }
-                csH += gamma * sH;
-                csL += gamma * sL;
+                sums[m][0] = sH << tc;
+                sums[m][1] = sL << tc;
+                const int r = rk0 + m;
                 const int lane_hi = g * 32 + 8 * (r >> 2) + (r & 3);
                 frag[(c * 8 + t) * 64 + lane_hi] = H;
                 frag[(c * 8 + t) * 64 + lane_hi + 4] = L;
             }
-        }
-        if (KS >= NT || tid < KS) {
-            atomicAdd(&cs[tid & 15], csH);
-            atomicAdd(&cs[16 + (tid & 15)], csL);
-        }
-    }
-    __syncthreads();
-    BS_TRACE(3);
-
-    // ---- sign stream x panel on the matrix cores
-    v16i acc[R][2];
+            // integer column sums of the quantised panel per rank and byte half: add up the
+            // lanes that hold the same ranks (lane bits above log2(16 / G)), then one LDS
+            // atomic per rank, half and wavefront
+            constexpr int RSTEP = 16 / G;   // lanes per full set of ranks
 #pragma unroll
-    for (int tl = 0; tl < R; ++tl)
+            for (int m = 0; m < G; ++m)
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+                for (int h = 0; h < 2; ++h) {
+                    int v = sums[m][h];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[tl][h][v] = 0;
-
-    uint4 uraw[R][2];
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        v4i wv[R];
-#pragma unroll
-        for (int tl = 0; tl < R; ++tl) {
-            wv[tl] = win[c % WCH][tl];
-            if (c + WCH < NCH && live[tl]) win[c % WCH][tl] = srow[tl][size_t(c + WCH) * 64];
-        }
-        if (c == NCH - 1) {   // U rows for the epilogue ride behind the last sign units
-#pragma unroll
-            for (int tl = 0; tl < R; ++tl) {
-                const int row = (live[tl] ? rt_base + tl : 0) * kTileRows + (lane & 31);
-                const uint4* up = reinterpret_cast<const uint4*>(blk + p.off_u + size_t(row) * 32);
-                uraw[tl][0] = up[0];
-                uraw[tl][1] = up[1];
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const v4i Tf = frag[(c * 8 + t) * 64 + lane];
-            const int mask = 0x01010101 << t;
-#pragma unroll
-            for (int tl = 0; tl < R; ++tl) {
-                const v4i B = wv[tl] & mask;
-                acc[tl][t >> 2] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Tf, B, acc[tl][t >> 2], 0, 0, 0);
-            }
-        }
-    }
-
-    // ---- epilogue: merge classes, undo S = 2B - 1, weight by U, reduce over ranks
-#ifdef BITSTACK_TRACE
-    if (acc[0][0][0] == 0x7fffffff) return;   // forces the accumulators before the stamp
-#endif
-    BS_TRACE(4);
-    {
-        const int part = lane >> 5, j = lane & 31;   // part 0: high bytes, 1: low bytes
-        const float dq = amax / (16.0f * kQMax);
-        int ncs[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) ncs[r] = cs[part * 16 + r] << 4;
-#pragma unroll
-        for (int tl = 0; tl < R; ++tl) {
-            if (live[tl]) {
-                const int row = (rt_base + tl) * kTileRows + j;
-                const uint4 ua = uraw[tl][0], ub = uraw[tl][1];
-                const unsigned uw[8] = {ua.x, ua.y, ua.z, ua.w, ub.x, ub.y, ub.z, ub.w};
-                float sum = 0.0f;
-#pragma unroll
-                for (int r2 = 0; r2 < 8; ++r2) {
-                    const __half2 h = *reinterpret_cast<const __half2*>(&uw[r2]);
-                    const int z0 = (((acc[tl][0][2 * r2] << 4) + acc[tl][1][2 * r2]) << 1) - ncs[2 * r2];
-                    const int z1 = (((acc[tl][0][2 * r2 + 1] << 4) + acc[tl][1][2 * r2 + 1]) << 1) - ncs[2 * r2 + 1];
-                    sum = fmaf(float(z0), __low2float(h), sum);
-                    sum = fmaf(float(z1), __high2float(h), sum);
+                    for (int off = RSTEP; off < 64; off <<= 1) v += __shfl_xor(v, off);
+                    sums[m][h] = v;
                 }
-                const float other = __shfl_xor(sum, 32);
-                // coherent (write-through) store: the reader may sit on another XCD
-                if (part == 0)
-                    __hip_atomic_store(&p.part[size_t(slot_i) * p.out + row], (256.0f * sum + other) * dq,
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane < RSTEP) {
+#pragma unroll
+                for (int m = 0; m < G; ++m) {
+                    atomicAdd(&csq[rk0 + m], sums[m][0]);
+                    atomicAdd(&csq[16 + rk0 + m], sums[m][1]);
+                }
             }
+        };
+
+        // ---- activation slab x/s in panel order (once per workgroup); the per-channel
+        // maxima of my first blocks and block 0's raw data are requested at the same time
+        if (ptid < 96) cs[ptid] = 0;
+        constexpr int NPRE = 8;   // blocks whose maxima are fetched before the first barrier
+        Raw ra, rb;
+        struct alignas(XP * 2) HVec {
+            __half h[XP];
+        };
+        HVec hv[NPRE];
+        {
+            float xv[XP], rv[XP];
+#pragma unroll
+            for (int m = 0; m < XP; ++m) {
+                const int idx = ptid * XP + m;
+                const int e = idx & 15, g = (idx >> 4) & 1, t = (idx >> 5) & 7, c = idx >> 8;
+                const int col = k0 + panel_col(c, t, g, e);
+                xv[m] = __half2float(p.x[col]);
+                rv[m] = p.rs[col];
+            }
+#pragma unroll
+            for (int k = 0; k < NPRE; ++k) {
+                const __half* vm = p.vmax + size_t(block_index(min(k, nb - 1))) * p.in + size_t(c0) * kChunkCols +
+                                   ptid * XP;
+                hv[k] = *reinterpret_cast<const HVec*>(vm);
+            }
+            ra = load_raw(0);
+#pragma unroll
+            for (int m = 0; m < XP; ++m) xs[ptid * XP + m] = xv[m] * rv[m];
+        }
+        __syncthreads();   // P1
+        BS_TRACE(1);
+        // ---- exact max |V[j][r] * xs[j]| over the slab for each of my blocks:
+        //      max_j |xs[j]| * max_r |V[j][r]|, the inner maximum stored at pack time
+        {
+            float xa[XP];
+#pragma unroll
+            for (int m = 0; m < XP; ++m) xa[m] = fabsf(xs[ptid * XP + m]);
+            for (int qb = 0; qb < nb; qb += NPRE) {
+                if (qb > 0) {
+#pragma unroll
+                    for (int k = 0; k < NPRE; ++k) {
+                        const __half* vm = p.vmax + size_t(block_index(min(qb + k, nb - 1))) * p.in +
+                                           size_t(c0) * kChunkCols + ptid * XP;
+                        hv[k] = *reinterpret_cast<const HVec*>(vm);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < NPRE; ++k) {
+                    if (qb + k < nb) {
+                        float a = 0.0f;
+#pragma unroll
+                        for (int m = 0; m < XP; ++m) a = fmaxf(a, xa[m] * __half2float(hv[k].h[m]));
+                        a = wave_max(a);
+                        if (lane == 0) amax_w[(wave - kConsumers) * kMaxBlocksPerWg + qb + k] = a;
+                    }
+                }
+            }
+        }
+        URows u0 = load_u(0);
+        rb = load_raw(1);
+        __syncthreads();   // P2
+        BS_TRACE(2);
+        quantise(0, ra);
+        store_u(0, u0);
+        __syncthreads();   // P3
+        BS_TRACE(3);
+        // interval q: stage block q + 1 (raw V already here), fetch block q + 2's raw V
+        for (int q = 0; q < nb; q += 2) {
+            BS_TRACE2(1, 2 * q);
+            if (ptid < 32) cs[((q + 2) % 3) * 32 + ptid] = 0;   // last read two barriers ago
+            ra = load_raw(q + 2);
+            if (q + 1 < nb) {
+                quantise(q + 1, rb);
+                store_u(q + 1, load_u(q + 1));   // producers have slack: latency exposed here is free
+            }
+            BS_TRACE2(1, 2 * q + 1);
+            __syncthreads();
+            if (q + 1 < nb) {
+                BS_TRACE2(1, 2 * q + 2);
+                if (ptid < 32) cs[((q + 3) % 3) * 32 + ptid] = 0;
+                rb = load_raw(q + 3);
+                if (q + 2 < nb) {
+                    quantise(q + 2, ra);
+                    store_u(q + 2, load_u(q + 2));
+                }
+                BS_TRACE2(1, 2 * q + 3);
+                __syncthreads();
+            }
+        }
+    } else {
+        // ============================================================== consumers
+        // sign window: win[c][tl] holds unit (chunk c, tile tl) of the current block until it
+        // is used, then the same unit of the next block
+        v4i win[NCH][R];
+        unsigned soff[R];   // byte offset of (tile, first chunk of slab, lane) inside a block
+        const unsigned sign_bytes = p.sign_bytes_total;   // bytes covered by the buffer descriptor
+        __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(p.blocks), 0, sign_bytes, 0x00020000);
+        // per-lane offset of (block q, tile tl, first chunk of the slab); for a block or tile
+        // that does not exist an offset just past the descriptor (reads as zero, no traffic;
+        // even unchecked it would stay inside the image)
+        const unsigned skip_off = sign_bytes + unsigned(lane) * 16u;
+        auto unit_off = [&](int q, int tl) -> unsigned {
+            const bool ok = q < nb && soff[tl] != 0xFFFFFFFFu;
+            return ok ? unsigned(block_index(q)) * unsigned(p.block_stride) + soff[tl] : skip_off;
+        };
+        float yacc[R];
+#pragma unroll
+        for (int tl = 0; tl < R; ++tl) {
+            const int rt = rs_i * (kConsumers * R) + wave * R + tl;
+            soff[tl] = rt < n_rt ? unsigned((size_t(rt) * nch_total + c0) * kUnitBytes) + unsigned(lane) * 16u
+                                 : 0xFFFFFFFFu;
+            yacc[tl] = 0.0f;
+        }
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int tl = 0; tl < R; ++tl)
+                win[c][tl] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, unit_off(0, tl) + c * kUnitBytes, 0, 0);
+
+        // Two tiles at a time (32 accumulator registers) against the whole slab, so that the
+        // sign window, not the accumulators, gets the registers.
+        auto compute = [&](int q) {
+            const v4i* frag = frag0 + (q & 1) * (FRAG_BYTES / 16);
+            const int part = lane >> 5;   // epilogue: 0 = high bytes, 1 = low bytes
+            const float dq = amax_of(q) / kQMax;
+            const int* csq = cs + (q % 3) * 32 + part * 16;
+            const uint4* ub = ulds + (q & 1) * (U_BYTES / 16) + (wave * R * kTileRows + (lane & 31)) * 2;
+#pragma unroll
+            for (int tp = 0; tp < R; tp += 2) {
+                v16i acc[2];
+#pragma unroll
+                for (int k = 0; k < 2; ++k)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[k][v] = 0;
+                unsigned noff[2];
+#pragma unroll
+                for (int k = 0; k < 2; ++k) noff[k] = unit_off(q + 1, tp + k);
+                v4i Tf = frag[lane];
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        // next fragment is requested before this one is used (LDS latency
+                        // hidden behind the matrix-core instructions of this one)
+                        v4i Tn = Tf;
+                        if (c * 8 + t + 1 < NCH * 8) Tn = frag[(c * 8 + t + 1) * 64 + lane];
+                        const int mask = 0x01010101 << (t & 3);
+                        if (t == 4) {   // high-nibble classes: bit 4+t' of a byte becomes bit t'
+#pragma unroll
+                            for (int k = 0; k < 2; ++k)
+#pragma unroll
+                                for (int w = 0; w < 4; ++w)
+                                    win[c][tp + k][w] = int(unsigned(win[c][tp + k][w]) >> 4);
+                        }
+#pragma unroll
+                        for (int k = 0; k < 2; ++k) {
+                            const v4i B = win[c][tp + k] & mask;
+                            acc[k] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Tf, B, acc[k], 0, 0, 0);
+                        }
+                        Tf = Tn;
+                    }
+                    // this chunk's window slots now take the same chunk of the next block (not
+                    // earlier: old and new contents would both need registers)
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int k = 0; k < 2; ++k)
+                        win[c][tp + k] =
+                            __builtin_amdgcn_raw_buffer_load_b128(rsrc, noff[k] + c * kUnitBytes, 0, 0);
+                }
+                // epilogue: undo S = 2B - 1, weight by U, reduce over ranks
+#pragma unroll
+                for (int k = 0; k < 2; ++k) {
+                    const int tl = tp + k;
+                    const uint4 ua = ub[tl * kTileRows * 2], uc = ub[tl * kTileRows * 2 + 1];
+                    const unsigned uw[8] = {ua.x, ua.y, ua.z, ua.w, uc.x, uc.y, uc.z, uc.w};
+                    float sum = 0.0f;
+#pragma unroll
+                    for (int r2 = 0; r2 < 8; ++r2) {
+                        const __half2 h = *reinterpret_cast<const __half2*>(&uw[r2]);
+                        const int z0 = (acc[k][2 * r2] << 1) - csq[2 * r2];
+                        const int z1 = (acc[k][2 * r2 + 1] << 1) - csq[2 * r2 + 1];
+                        sum = fmaf(float(z0), __low2float(h), sum);
+                        sum = fmaf(float(z1), __high2float(h), sum);
+                    }
+                    const float other = __shfl_xor(sum, 32);
+                    yacc[tl] = fmaf(256.0f * sum + other, dq, yacc[tl]);   // meaningful in lanes 0..31
+                }
+            }
+        };
+
+        __syncthreads();   // P1
+        BS_TRACE(1);
+        __syncthreads();   // P2
+        BS_TRACE(2);
+        __syncthreads();   // P3
+        BS_TRACE(3);
+        for (int q = 0; q < nb; ++q) {
+            BS_TRACE2(0, 2 * q);
+            compute(q);
+            BS_TRACE2(0, 2 * q + 1);
+            __syncthreads();
+        }
+        BS_TRACE(4);
+        // ---- partial sums out (agent-scope, write-through stores: the reader may sit on another XCD)
+#pragma unroll
+        for (int tl = 0; tl < R; ++tl) {
+            const int row = row0 + (wave * R + tl) * kTileRows + lane;
+            if (lane < 32 && row < p.out)
+                __hip_atomic_store(&p.part[size_t(slot_i) * p.out + row], yacc[tl], __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 
-    // ---- the last workgroup of this row slab adds the partial rows and stores y
+    // ---- the last workgroup of this row slab adds the partial rows and stores y.
+    // Ordering: every wave's stores above are complete when it passes the barrier
+    // (workgroup-scope release = wait for the vector memory counter), they are
+    // write-through, and the counter increment is issued only after that; the
+    // finishing workgroup reads the rows back with agent-scope loads after an
+    // agent-scope acquire.  No cache-wide write-back or invalidate is paid by the
+    // other workgroups (those cost more than the whole sign stream of a block).
     __syncthreads();
     BS_TRACE(5);
     if (tid == 0) {
-        const unsigned expected = unsigned(p.n_ks) * unsigned(p.n_loaded);
-        // Release only: the partial rows were written with agent-scope (write-through)
-        // stores and are read back with agent-scope loads, so no cache needs
-        // invalidating here; an acquire (which drops this XCD's L2 contents for every
-        // workgroup sharing it) is paid by the one finishing workgroup alone.
-        const unsigned old = EARLY ? __hip_atomic_fetch_add(&p.ctr[rs_i], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT)
-                                   : __hip_atomic_fetch_add(&p.ctr[rs_i], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned expected = unsigned(p.n_ks) * unsigned(p.n_bg);
+        const unsigned old = __hip_atomic_fetch_add(&p.ctr[rs_i], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         *flag = (old + 1u == expected) ? 1u : 0u;
     }
     __syncthreads();
     BS_TRACE(6);
     if (*flag) {
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        const int row0 = rs_i * RS;
-        const int nslots = p.n_ks * p.n_loaded;
+        const int nslots = p.n_ks * p.n_bg;
         for (int i = tid; i < RS && row0 + i < p.out; i += NT) {
             const float* src = p.part + row0 + i;
             float tot = 0.0f;
-            for (int sl = 0; sl < nslots; sl += 16) {   // 16 loads in flight, fixed summation order
-                float v[16];
+            for (int sl = 0; sl < nslots; sl += 64) {   // 64 loads in flight, fixed summation order
+                float v[64];
 #pragma unroll
-                for (int q = 0; q < 16; ++q)
-                    v[q] = (sl + q < nslots) ? __hip_atomic_load(src + size_t(sl + q) * p.out, __ATOMIC_RELAXED,
+                for (int k = 0; k < 64; ++k)
+                    v[k] = (sl + k < nslots) ? __hip_atomic_load(src + size_t(sl + k) * p.out, __ATOMIC_RELAXED,
                                                                  __HIP_MEMORY_SCOPE_AGENT)
                                              : 0.0f;
 #pragma unroll
-                for (int q = 0; q < 16; ++q) tot += v[q];
+                for (int k = 0; k < 64; ++k) tot += v[k];
             }
             store_y(p, size_t(row0 + i), tot);
         }
@@ -485,45 +675,56 @@ __global__ __launch_bounds__(WAVES * 64, OCC) void k_decode(KParams p) {
     BS_TRACE(7);
 }
 
-template <int WAVES, int KS, int WIN, int OCC, bool EARLY>
-static hipError_t launch_decode_t(KParams p, hipStream_t st) {
-    constexpr int RS = WAVES * 2 * kTileRows;
-    p.n_rs = (p.out + RS - 1) / RS;
+template <int KS>
+static hipError_t launch_decode_t(KParams p, int bg_req, hipStream_t st) {
+    p.n_rs = (p.out + kDecodeRows - 1) / kDecodeRows;
     p.n_ks = p.in / KS;
-    const size_t smem = size_t(KS) * 36 + 128 + 64 + 16;
+    // block groups: enough workgroups to fill the chip once (one per compute unit), few
+    // enough that each walks through several blocks and amortises its prologue and tail
+    const int pairs = p.n_rs * p.n_ks;
+    int bg = bg_req;
+    if (bg <= 0) {
+        // largest group count that still fits on the chip in one round; among those prefer
+        // one that gives every workgroup the same number of blocks
+        bg = 256 / pairs;
+        if (bg < 1) bg = 1;
+        if (bg > p.n_loaded) bg = p.n_loaded;
+        for (int cand = bg; cand >= 1 && cand * 4 >= bg * 3; --cand)
+            if (p.n_loaded % cand == 0) {
+                bg = cand;
+                break;
+            }
+    }
+    if (bg > p.n_loaded) bg = p.n_loaded;
+    while ((p.n_loaded + bg - 1) / bg > kMaxBlocksPerWg) ++bg;
+    p.n_bg = bg;
+    if (p.n_rs > kCounterSlots || p.n_ks * bg > p.part_slots) return hipErrorInvalidValue;
+    const size_t smem = size_t(KS) * 68 + 2 * size_t(kDecodeRows) * 32 + size_t(kProducers) * kMaxBlocksPerWg * 4 +
+                        96 * 4 + 16;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<WAVES, KS, WIN, OCC, EARLY>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<KS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(smem));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const unsigned grid = unsigned(p.n_rs) * unsigned(p.n_ks) * unsigned(p.n_loaded);
-    hipLaunchKernelGGL((k_decode<WAVES, KS, WIN, OCC, EARLY>), dim3(grid), dim3(WAVES * 64), smem, st, p);
+    const unsigned grid = unsigned(pairs) * unsigned(bg);
+    hipLaunchKernelGGL((k_decode<KS>), dim3(grid), dim3((kConsumers + kProducers) * 64), smem, st, p);
     return hipGetLastError();
 }
 
 hipError_t launch_decode(const LaunchArgs& a, hipStream_t st) {
     KParams p = make_params(a);
-    int waves = decode_tuning().waves, ks = decode_tuning().kslab;
-    if (ks == 0) ks = (p.in % 2048 == 0) ? 2048 : a.geo.min_slab;
+    const DecodeTuning& tn = decode_tuning();
+    int ks = tn.kslab;
+    if (ks == 0) ks = a.geo.min_slab;
     if (ks < a.geo.min_slab || p.in % ks) return hipErrorInvalidValue;   // workspace is sized for min_slab
-    if (waves == 0) waves = (ks == 256) ? 4 : (p.out >= 2048 ? 8 : 4);
-    if ((p.out + waves * 64 - 1) / (waves * 64) > kCounterSlots) return hipErrorInvalidValue;
-#define BS_CASE(W, K, WN, OC)                                                        \
-    if (waves == W && ks == K)                                                        \
-        return decode_tuning().variant ? launch_decode_t<W, K, WN, OC, false>(p, st)  \
-                                       : launch_decode_t<W, K, WN, OC, true>(p, st)
-    BS_CASE(16, 1024, 4, 4);
-    BS_CASE(16, 512, 2, 4);
-    BS_CASE(8, 2048, 4, 4);
-    BS_CASE(8, 1024, 4, 4);
-    BS_CASE(8, 512, 2, 4);
-    BS_CASE(4, 2048, 4, 2);
-    BS_CASE(4, 1024, 4, 4);
-    BS_CASE(4, 512, 2, 4);
-    BS_CASE(4, 256, 1, 4);
-#undef BS_CASE
+    const size_t sign_span = size_t(a.geo.n) * a.geo.block_stride;
+    if (sign_span + 4096 >= (size_t(1) << 32)) return hipErrorInvalidValue;   // 32-bit buffer offsets
+    p.sign_bytes_total = unsigned(sign_span);
+    if (ks == 1024) return launch_decode_t<1024>(p, tn.bgroups, st);
+    if (ks == 512) return launch_decode_t<512>(p, tn.bgroups, st);
+    if (ks == 256) return launch_decode_t<256>(p, tn.bgroups, st);
     return hipErrorInvalidValue;
 }
 

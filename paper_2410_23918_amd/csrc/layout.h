@@ -23,9 +23,12 @@
 // U rows.  Plain row-major [out][16].
 //
 // The image of a whole stack is
-//   [ 1/s : in floats ][ block 0 ] ... [ block n-1 ][ partial sums ][ counters ]
-// with every part 256-byte aligned.  The partial-sum workspace holds one fp32 row
-// of `out` values per (block, column slab) workgroup column of the decode kernel.
+//   [ 1/s : in floats ][ block 0 ] ... [ block n-1 ][ row maxima ][ partial sums ][ counters ]
+// with every part 256-byte aligned.  "Row maxima" is derived data, not part of a
+// block: per block and input channel j, max_r |V[j][r]| as fp16 in panel order; it
+// lets the decode kernel find the exact max |V[j][r] * x[j]/s[j]| of a column slab
+// from one value per channel instead of sixteen.  The partial-sum workspace holds
+// one fp32 row of `out` values per workgroup that shares a row slab.
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
@@ -51,6 +54,7 @@ struct Geometry {
     size_t block_stride; // == Eq. 9 bytes
     size_t off_v;        // inside a block: V panels
     size_t off_u;        // inside a block: U rows
+    size_t off_vmax;     // fp16[n][in], max_r |V[j][r]| in panel order
     size_t off_part;     // float[part_slots][out] split-accumulation workspace
     int part_slots;      // n * (in / min_slab)
     int min_slab;        // smallest column slab the decode kernel may use with this image
@@ -75,7 +79,8 @@ BS_HD Geometry make_geometry(int out, int in, int n, int max_batch) {
     g.off_blocks = align256(size_t(in) * 4);
     g.min_slab = (in % 1024 == 0) ? 1024 : (in % 512 == 0) ? 512 : 256;
     g.part_slots = (n > 0 ? n : 1) * (in / g.min_slab);
-    g.off_part = align256(g.off_blocks + size_t(n) * g.block_stride);
+    g.off_vmax = align256(g.off_blocks + size_t(n) * g.block_stride);
+    g.off_part = align256(g.off_vmax + size_t(n) * size_t(in) * 2);
     g.off_ctr = align256(g.off_part + size_t(g.part_slots) * size_t(out) * 4);
     g.total = align256(g.off_ctr + size_t(kCounterSlots) * 4);
     return g;
@@ -96,6 +101,13 @@ BS_HD size_t v_index(int col, int r) {
     int g = c / 128, w = (c % 128) / 32, b = (c % 32) / 8, t = c % 8;
     int e = w * 4 + b;
     return ((((size_t(ch) * 8 + t) * 2 + g) * 16 + r) * 16) + size_t(e);
+}
+
+// index of channel col in a per-channel array kept in panel order
+BS_HD size_t panel_index(int col) {
+    int ch = col / kChunkCols, c = col % kChunkCols;
+    int g = c / 128, w = (c % 128) / 32, b = (c % 32) / 8, t = c % 8;
+    return ((size_t(ch) * 8 + t) * 2 + g) * 16 + size_t(w * 4 + b);
 }
 
 // inverse view used by the kernels: column of (chunk, t, g, e)

@@ -99,7 +99,7 @@ def test_repeat_calls_leave_workspace_clean(B):
 
 # ------------------------------------------------------------------ edge shapes
 @pytest.mark.parametrize("out,inn,n", [(32, 256, 1), (96, 768, 3), (160, 1024, 2), (1056, 512, 2),
-                                       (192, 1536, 2), (64, 2048, 2), (2080, 2048, 1)])
+                                       (192, 1536, 2), (64, 2048, 5), (2080, 2048, 3)])
 def test_small_and_ragged_shapes(B, out, inn, n):
     st = synth_stack(3, out, inn, n)
     ps = _pack(B, st, max_batch=3)
@@ -108,17 +108,19 @@ def test_small_and_ragged_shapes(B, out, inn, n):
     y = _run(B, ps, x, n, B.KERNEL_REFERENCE)
     assert O.relative_error(y, ref) <= TOL
     min_slab = 1024 if inn % 1024 == 0 else 512 if inn % 512 == 0 else 256
-    for waves in (4, 8, 16):
-        for ks in (256, 512, 1024, 2048):
-            if inn % ks or ks < min_slab or (ks == 256 and waves != 4) or (ks == 2048 and waves == 16):
-                continue
-            B.set_option(B.OPT_DECODE_WAVES, waves); B.set_option(B.OPT_DECODE_KSLAB, ks)
+    for ks in (256, 512, 1024):
+        if inn % ks or ks < min_slab:
+            continue
+        for bg in (0, 1, n):
+            B.set_option(B.OPT_DECODE_KSLAB, ks)
+            B.set_option(B.OPT_DECODE_BGROUPS, bg)
             try:
                 y1 = _run(B, ps, x[:1], n, B.KERNEL_DECODE)
             finally:
-                B.set_option(B.OPT_DECODE_WAVES, 0); B.set_option(B.OPT_DECODE_KSLAB, 0)
+                B.set_option(B.OPT_DECODE_KSLAB, 0)
+                B.set_option(B.OPT_DECODE_BGROUPS, 0)
             err = O.relative_error(y1, ref[:1])
-            print(f"{out}x{inn} waves={waves} ks={ks}: {err:.2e}", flush=True)
+            print(f"{out}x{inn} ks={ks} bgroups={bg}: {err:.2e}", flush=True)
             assert err <= TOL
 
 
