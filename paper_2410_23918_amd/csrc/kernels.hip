@@ -220,6 +220,15 @@ constexpr int kProducers = 4;      // wavefronts that build the panel fragments
 constexpr int kTilesPerWave = 4;   // 32-row tiles per consumer wavefront
 constexpr int kDecodeRows = kConsumers * kTilesPerWave * kTileRows;   // rows per workgroup (1024)
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load of the wavefront (its fence covers all address spaces), which
+// would drain the consumers' sign window at every block boundary.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 __device__ __forceinline__ float wave_max(float v) {
     for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
     return v;
@@ -426,32 +435,30 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
         // maxima of my first blocks and block 0's raw data are requested at the same time
         if (ptid < 96) cs[ptid] = 0;
         constexpr int NPRE = 8;   // blocks whose maxima are fetched before the first barrier
-        Raw ra, rb;
         struct alignas(XP * 2) HVec {
             __half h[XP];
         };
         HVec hv[NPRE];
-        {
-            float xv[XP], rv[XP];
+        float xv[XP], rv[XP];
 #pragma unroll
-            for (int m = 0; m < XP; ++m) {
-                const int idx = ptid * XP + m;
-                const int e = idx & 15, g = (idx >> 4) & 1, t = (idx >> 5) & 7, c = idx >> 8;
-                const int col = k0 + panel_col(c, t, g, e);
-                xv[m] = __half2float(p.x[col]);
-                rv[m] = p.rs[col];
-            }
-#pragma unroll
-            for (int k = 0; k < NPRE; ++k) {
-                const __half* vm = p.vmax + size_t(block_index(min(k, nb - 1))) * p.in + size_t(c0) * kChunkCols +
-                                   ptid * XP;
-                hv[k] = *reinterpret_cast<const HVec*>(vm);
-            }
-            ra = load_raw(0);
-#pragma unroll
-            for (int m = 0; m < XP; ++m) xs[ptid * XP + m] = xv[m] * rv[m];
+        for (int m = 0; m < XP; ++m) {
+            const int idx = ptid * XP + m;
+            const int e = idx & 15, g = (idx >> 4) & 1, t = (idx >> 5) & 7, c = idx >> 8;
+            const int col = k0 + panel_col(c, t, g, e);
+            xv[m] = __half2float(p.x[col]);
+            rv[m] = p.rs[col];
         }
-        __syncthreads();   // P1
+#pragma unroll
+        for (int k = 0; k < NPRE; ++k) {
+            const __half* vm = p.vmax + size_t(block_index(min(k, nb - 1))) * p.in + size_t(c0) * kChunkCols +
+                               ptid * XP;
+            hv[k] = *reinterpret_cast<const HVec*>(vm);
+        }
+        Raw ra = load_raw(0);
+        const URows u0 = load_u(0);
+#pragma unroll
+        for (int m = 0; m < XP; ++m) xs[ptid * XP + m] = xv[m] * rv[m];
+        lds_barrier();   // P1
         BS_TRACE(1);
         // ---- exact max |V[j][r] * xs[j]| over the slab for each of my blocks:
         //      max_j |xs[j]| * max_r |V[j][r]|, the inner maximum stored at pack time
@@ -480,13 +487,12 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
                 }
             }
         }
-        URows u0 = load_u(0);
-        rb = load_raw(1);
-        __syncthreads();   // P2
+        lds_barrier();   // P2
         BS_TRACE(2);
+        Raw rb = load_raw(1);
         quantise(0, ra);
         store_u(0, u0);
-        __syncthreads();   // P3
+        lds_barrier();   // P3
         BS_TRACE(3);
         // interval q: stage block q + 1 (raw V already here), fetch block q + 2's raw V
         for (int q = 0; q < nb; q += 2) {
@@ -498,7 +504,7 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
                 store_u(q + 1, load_u(q + 1));   // producers have slack: latency exposed here is free
             }
             BS_TRACE2(1, 2 * q + 1);
-            __syncthreads();
+            lds_barrier();
             if (q + 1 < nb) {
                 BS_TRACE2(1, 2 * q + 2);
                 if (ptid < 32) cs[((q + 3) % 3) * 32 + ptid] = 0;
@@ -508,7 +514,7 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
                     store_u(q + 2, load_u(q + 2));
                 }
                 BS_TRACE2(1, 2 * q + 3);
-                __syncthreads();
+                lds_barrier();
             }
         }
     } else {
@@ -536,11 +542,6 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
                                  : 0xFFFFFFFFu;
             yacc[tl] = 0.0f;
         }
-#pragma unroll
-        for (int c = 0; c < NCH; ++c)
-#pragma unroll
-            for (int tl = 0; tl < R; ++tl)
-                win[c][tl] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, unit_off(0, tl) + c * kUnitBytes, 0, 0);
 
         // Two tiles at a time (32 accumulator registers) against the whole slab, so that the
         // sign window, not the accumulators, gets the registers.
@@ -613,17 +614,24 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
             }
         };
 
-        __syncthreads();   // P1
+        lds_barrier();   // P1
         BS_TRACE(1);
-        __syncthreads();   // P2
+        // The sign stream starts only now: requested at kernel entry it would fill the memory
+        // queues ahead of the few loads the producers' prologue is waiting for.
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int tl = 0; tl < R; ++tl)
+                win[c][tl] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, unit_off(0, tl) + c * kUnitBytes, 0, 0);
+        lds_barrier();   // P2
         BS_TRACE(2);
-        __syncthreads();   // P3
+        lds_barrier();   // P3
         BS_TRACE(3);
         for (int q = 0; q < nb; ++q) {
             BS_TRACE2(0, 2 * q);
             compute(q);
             BS_TRACE2(0, 2 * q + 1);
-            __syncthreads();
+            lds_barrier();
         }
         BS_TRACE(4);
         // ---- partial sums out (agent-scope, write-through stores: the reader may sit on another XCD)
