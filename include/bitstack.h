@@ -65,9 +65,8 @@ enum { BITSTACK_Y_F16 = 0, BITSTACK_Y_F32 = 1 };
 /* kernel selectors (bitstack_linear_select); AUTO is what bitstack_linear uses */
 enum {
     BITSTACK_KERNEL_AUTO      = 0,
-    BITSTACK_KERNEL_REFERENCE = 1, /* plain vector-ALU kernel, any batch <= max_batch */
-    BITSTACK_KERNEL_DECODE    = 2, /* matrix-core sign-stream kernel, batch 1         */
-    BITSTACK_KERNEL_PANEL     = 3  /* tile-reconstructing matrix-core kernel, batch >= 2 */
+    BITSTACK_KERNEL_REFERENCE = 1, /* plain vector-ALU kernel, any batch <= max_batch            */
+    BITSTACK_KERNEL_DECODE    = 2  /* matrix-core sign-stream kernel, one launch per token       */
 };
 
 /* Bytes of one residual block: (out*in + 16*k*(out+in)) / 8, Eq. (9) of the
@@ -149,8 +148,7 @@ int bitstack_linear_many(const bitstack_job_t* jobs, int count, int repeat, bits
 int bitstack_linear_batched(const void* x, int batch, const bitstack_weight_t* blocks,
                             int n_loaded, void* y, int y_dtype, bitstack_stream_t stream);
 
-/* As bitstack_linear_batched with an explicit kernel choice (tests, benchmarks).
- * Returns BITSTACK_E_ARG when the chosen kernel does not support the batch. */
+/* As bitstack_linear_batched with an explicit kernel choice (tests, benchmarks). */
 int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* blocks,
                            int n_loaded, void* y, int y_dtype, int kernel,
                            bitstack_stream_t stream);

@@ -215,16 +215,23 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w,
     if (n_loaded == 0) {
         e = launch_zero(a, st);
     } else {
-        if (kernel == BITSTACK_KERNEL_AUTO)
-            kernel = (batch == 1) ? BITSTACK_KERNEL_DECODE : BITSTACK_KERNEL_REFERENCE;
+        if (kernel == BITSTACK_KERNEL_AUTO) kernel = BITSTACK_KERNEL_DECODE;
         switch (kernel) {
             case BITSTACK_KERNEL_REFERENCE:
                 e = launch_reference(a, st);
                 break;
-            case BITSTACK_KERNEL_DECODE:
-                if (batch != 1) return BITSTACK_E_ARG;
-                e = launch_decode(a, st);
+            case BITSTACK_KERNEL_DECODE: {
+                // one launch per token: the decode kernel handles a single activation vector
+                const size_t ybytes = size_t(g.out) * (a.y_f32 ? 4 : 2);
+                LaunchArgs t = a;
+                t.batch = 1;
+                for (int b = 0; b < batch && e == hipSuccess; ++b) {
+                    t.x = static_cast<const unsigned char*>(x) + size_t(b) * g.in * 2;
+                    t.y = static_cast<unsigned char*>(y) + size_t(b) * ybytes;
+                    e = launch_decode(t, st);
+                }
                 break;
+            }
             default:
                 return BITSTACK_E_ARG;
         }
