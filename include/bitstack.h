@@ -66,7 +66,8 @@ enum { BITSTACK_Y_F16 = 0, BITSTACK_Y_F32 = 1 };
 enum {
     BITSTACK_KERNEL_AUTO      = 0,
     BITSTACK_KERNEL_REFERENCE = 1, /* plain vector-ALU kernel, any batch <= max_batch            */
-    BITSTACK_KERNEL_DECODE    = 2  /* matrix-core sign-stream kernel, one launch per token       */
+    BITSTACK_KERNEL_DECODE    = 2, /* matrix-core sign-stream kernel, one launch per token       */
+    BITSTACK_KERNEL_PANEL     = 3  /* weight tile rebuilt in LDS + matrix-core GEMM, any batch   */
 };
 
 /* Bytes of one residual block: (out*in + 16*k*(out+in)) / 8, Eq. (9) of the

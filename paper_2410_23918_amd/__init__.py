@@ -6,7 +6,7 @@ marshals arguments.  PyTorch supplies device memory and streams.
 from .binding import (  # noqa: F401
     BitStackError,
     PackedStack,
-    KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE,
+    KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL,
     OPT_DECODE_KSLAB, OPT_DECODE_BGROUPS,
     block_bytes,
     lib,

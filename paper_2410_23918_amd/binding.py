@@ -10,7 +10,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libbitstack.so")
 _lib = None
 
-KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE = 0, 1, 2
+KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL = 0, 1, 2, 3
 Y_F16, Y_F32 = 0, 1
 OPT_DECODE_KSLAB, OPT_DECODE_BGROUPS = 2, 3
 

@@ -215,7 +215,20 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w,
     if (n_loaded == 0) {
         e = launch_zero(a, st);
     } else {
-        if (kernel == BITSTACK_KERNEL_AUTO) kernel = BITSTACK_KERNEL_DECODE;
+        if (kernel == BITSTACK_KERNEL_AUTO) {
+            // Per-token decode launches stream the blocks once per token; the panel kernel
+            // rebuilds the weight once per 64-128 tokens at a fixed cost per (block, 64 x 256
+            // tile).  Rates measured on MI355X: ~2.4 GB/ms of block stream plus ~15 us per
+            // decode launch; ~1.4 us per block and tile column when every row tile has its
+            // own compute unit.
+            const double blk_bytes = double(g.block_stride);
+            const double t_decode = batch * (15.0 + n_loaded * blk_bytes / 2.4e6);
+            const int row_tiles = (g.out + 63) / 64;
+            const int rounds = (row_tiles + 255) / 256;
+            const int tok_tiles = batch > 64 ? (batch + 127) / 128 : 1;
+            const double t_panel = 1.4 * n_loaded * (g.in / 256) * rounds * tok_tiles;
+            kernel = (batch == 1 || t_decode <= t_panel) ? BITSTACK_KERNEL_DECODE : BITSTACK_KERNEL_PANEL;
+        }
         switch (kernel) {
             case BITSTACK_KERNEL_REFERENCE:
                 e = launch_reference(a, st);
@@ -232,6 +245,9 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w,
                 }
                 break;
             }
+            case BITSTACK_KERNEL_PANEL:
+                e = launch_panel(a, st);
+                break;
             default:
                 return BITSTACK_E_ARG;
         }

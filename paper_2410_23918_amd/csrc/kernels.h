@@ -27,5 +27,6 @@ hipError_t launch_stream_read(const void* buf, size_t bytes, void* sink, int blo
 hipError_t launch_zero(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_reference(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_decode(const LaunchArgs& a, hipStream_t st);
+hipError_t launch_panel(const LaunchArgs& a, hipStream_t st);
 
 }  // namespace bitstack

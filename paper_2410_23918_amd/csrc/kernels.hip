@@ -30,6 +30,7 @@
 #include <type_traits>
 
 #include "kernels.h"
+#include "kparams.h"
 #include "layout.h"
 
 namespace bitstack {
@@ -66,53 +67,6 @@ extern "C" int bitstack_debug_trace(unsigned long long* host, int n) {
 DecodeTuning& decode_tuning() {
     static DecodeTuning t = {0, 0};
     return t;
-}
-
-struct KParams {
-    const __half* x;      // [batch][in]
-    void* y;              // [batch][out]
-    const float* rs;      // [in]   1/s
-    const unsigned char* blocks;
-    size_t block_stride, off_v, off_u;
-    const __half* vmax;   // [n][in] max_r |V[j][r]|, panel order
-    float* part;          // [part_slots][out] partial sums
-    int part_slots;
-    unsigned sign_bytes_total;  // n * block_stride: extent of the buffer descriptor over the blocks
-    int n_bg;             // block groups: a workgroup walks blocks bg, bg + n_bg, ...
-    unsigned* ctr;        // arrival counters (zero between calls)
-    int out, in, batch, n_loaded;
-    int n_rs, n_ks;       // row slabs, column slabs per block
-    int y_f32;
-};
-
-static KParams make_params(const LaunchArgs& a) {
-    KParams p;
-    p.x = static_cast<const __half*>(a.x);
-    p.y = a.y;
-    p.rs = reinterpret_cast<const float*>(a.image + a.geo.off_rs);
-    p.blocks = a.image + a.geo.off_blocks;
-    p.block_stride = a.geo.block_stride;
-    p.off_v = a.geo.off_v;
-    p.off_u = a.geo.off_u;
-    p.vmax = reinterpret_cast<const __half*>(a.image + a.geo.off_vmax);
-    p.part = reinterpret_cast<float*>(a.image + a.geo.off_part);
-    p.part_slots = a.geo.part_slots;
-    p.n_bg = 1;
-    p.ctr = reinterpret_cast<unsigned*>(a.image + a.geo.off_ctr);
-    p.out = a.geo.out;
-    p.in = a.geo.in;
-    p.batch = a.batch;
-    p.n_loaded = a.n_loaded;
-    p.n_rs = p.n_ks = 0;
-    p.y_f32 = a.y_f32 ? 1 : 0;
-    return p;
-}
-
-__device__ __forceinline__ void store_y(const KParams& p, size_t idx, float v) {
-    if (p.y_f32)
-        static_cast<float*>(p.y)[idx] = v;
-    else
-        static_cast<__half*>(p.y)[idx] = __float2half_rn(v);
 }
 
 // ---------------------------------------------------------------- y = 0 (no block loaded)

@@ -107,6 +107,11 @@ def test_small_and_ragged_shapes(B, out, inn, n):
     ref = O.forward_dense(st, x, n)
     y = _run(B, ps, x, n, B.KERNEL_REFERENCE)
     assert O.relative_error(y, ref) <= TOL
+    for dt in ("f16", "f32"):
+        y = _run(B, ps, x, n, B.KERNEL_PANEL, dt)
+        err = O.relative_error(y, ref)
+        print(f"{out}x{inn} panel kernel B=3 {dt}: {err:.2e}", flush=True)
+        assert err <= TOL
     min_slab = 1024 if inn % 1024 == 0 else 512 if inn % 512 == 0 else 256
     for ks in (256, 512, 1024):
         if inn % ks or ks < min_slab:
@@ -173,6 +178,11 @@ def test_cfg3_llama_mlp_batches(B, out, inn):
         y = _run(B, ps, x[:b], 16, B.KERNEL_AUTO)
         err = O.relative_error(y, ref[:b])
         print(f"cfg3 {out}x{inn} B={b} auto: {err:.2e}", flush=True)
+        assert err <= TOL
+    for b in (1, 16):
+        y = _run(B, ps, x[:b], 16, B.KERNEL_PANEL)
+        err = O.relative_error(y, ref[:b])
+        print(f"cfg3 {out}x{inn} B={b} panel kernel: {err:.2e}", flush=True)
         assert err <= TOL
     y = _run(B, ps, x[:16], 16, B.KERNEL_REFERENCE, "f32")
     err = O.relative_error(y, ref[:16])
