@@ -110,6 +110,47 @@ def cpu_baseline(stack, x, n_loaded, block_stream_bytes, budget_s=12.0):
     }
 
 
+def decoder_token(B, torch, dev, layers=32, n_pack=24):
+    """Config 4: one token through 7 linears x 32 layers, per-matrix n_loaded ~ U{8..24}.
+    One layer's seven stacks are generated on the host; every layer gets its own packed
+    device copy (distinct memory is what the HBM stream sees)."""
+    from workloads import synth as W
+    shapes = W.llama3_8b_layer_shapes()
+    nl = W.variable_n_loaded(W.rng_for(4, 0), layers * len(shapes))
+    t0 = time.time()
+    host = []
+    for m, (name, o, i) in enumerate(shapes):
+        st = build_stack(o, i, n_pack, False, 4)
+        host.append((st.sign_words(), st.U, st.V, st.s))
+    packed = [[B.PackedStack(*host[m]) for m in range(len(shapes))] for _ in range(layers)]
+    log(f"[bench] decoder: generated and packed {layers * len(shapes)} stacks (n={n_pack}) in {time.time() - t0:.0f} s")
+    xs = {i: torch.from_numpy(W.activations(W.rng_for(4, 100, 1, i), 1, i)[0]).to(dev) for i in (4096, 14336)}
+    items, total_bytes = [], 0
+    for l in range(layers):
+        for m, (name, o, i) in enumerate(shapes):
+            n_l = int(nl[l * len(shapes) + m])
+            y = torch.empty(o, dtype=torch.float16, device=dev)
+            items.append((xs[i], packed[l][m], n_l, y))
+            total_bytes += n_l * B.block_bytes(o, i)
+    jobs = B.make_jobs(items)
+    B.linear_many(jobs, 2)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    reps = 5
+    e0.record()
+    B.linear_many(jobs, reps)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    gbs = total_bytes / ms / 1e6
+    log(f"[bench] decoder token: {len(items)} linears, {total_bytes / 1e9:.2f} GB of blocks, {ms:.3f} ms/token, "
+        f"{gbs:.0f} GB/s ({gbs / HBM_PEAK_GBS * 100:.1f}% of 8 TB/s)")
+    return {"linears": len(items), "block_stream_bytes": total_bytes, "ms_per_token": round(ms, 4),
+            "GBps": round(gbs, 1), "pct_of_hbm_peak": round(gbs / HBM_PEAK_GBS * 100, 2),
+            "n_loaded": "U{8..24} per matrix, seeded"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,6 +158,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--copies", type=int, default=16, help="separately packed copies to rotate over")
     ap.add_argument("--table", action="store_true", help="also time the MLP shapes (stderr)")
+    ap.add_argument("--decoder", action="store_true",
+                    help="also time one token through all 224 linears of a Llama-3-8B-shaped decoder with "
+                         "per-matrix n_loaded ~ U{8..24} (config 4; needs ~25 GB of HBM, takes a minute to pack)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a 256 MiB read probe and a 256 MiB device copy (known sizes that scale the "
@@ -193,6 +237,10 @@ def main():
                 f"({bb / t / 1e9 / HBM_PEAK_GBS * 100:.1f}% of 8 TB/s)")
             del pst, j2
 
+    extra = {}
+    if args.decoder:
+        extra["decoder_token"] = decoder_token(B, torch, dev)
+
     result = {
         "metric": "effective block-stream GB/s, batch-1 decode, n=16 k=16, Llama-3-8B 4096x4096 projection",
         "value": round(value, 2),
@@ -227,6 +275,8 @@ def main():
             "avg_launch_us_event_pairs": round(kmean * 1e6, 3),
         },
     }
+    if extra:
+        result["config"].update(extra)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(st, xh, n, bytes_per_call)
     print(json.dumps(result), flush=True)

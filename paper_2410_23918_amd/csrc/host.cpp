@@ -216,17 +216,23 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w,
         e = launch_zero(a, st);
     } else {
         if (kernel == BITSTACK_KERNEL_AUTO) {
-            // Per-token decode launches stream the blocks once per token; the panel kernel
-            // rebuilds the weight once per 64-128 tokens at a fixed cost per (block, 64 x 256
-            // tile).  Rates measured on MI355X: ~2.4 GB/ms of block stream plus ~15 us per
-            // decode launch; ~1.4 us per block and tile column when every row tile has its
-            // own compute unit.
+            // Per-token decode launches stream the blocks once per token.  The batch path has two
+            // kernels: up to 64 tokens, signed tiles are rebuilt per group of 32 tokens at ~1 us
+            // per block and pair of 256-column chunks of a 64-row tile; beyond that a weight tile
+            // is rebuilt once per 512 tokens at ~1.1 us per block and chunk.  Rates measured on
+            // MI355X; decode: ~2.4 GB/ms of block stream plus ~15 us per launch.
             const double blk_bytes = double(g.block_stride);
             const double t_decode = batch * (15.0 + n_loaded * blk_bytes / 2.4e6);
             const int row_tiles = (g.out + 63) / 64;
-            const int rounds = (row_tiles + 255) / 256;
-            const int tok_tiles = batch > 64 ? (batch + 127) / 128 : 1;
-            const double t_panel = 1.4 * n_loaded * (g.in / 256) * rounds * tok_tiles;
+            const int chunks = g.in / 256;
+            double t_panel;
+            if (batch <= 64) {
+                const int wgs = row_tiles * ((batch + 31) / 32);
+                t_panel = ((wgs + 255) / 256) * (15.0 + 1.0 * n_loaded * ((chunks + 1) / 2));
+            } else {
+                const int wgs = row_tiles * ((batch + 511) / 512);
+                t_panel = ((wgs + 255) / 256) * (1.1 * n_loaded * chunks + 0.6 * chunks * ((batch < 512 ? batch : 512) / 128.0));
+            }
             kernel = (batch == 1 || t_decode <= t_panel) ? BITSTACK_KERNEL_DECODE : BITSTACK_KERNEL_PANEL;
         }
         switch (kernel) {

@@ -174,15 +174,6 @@ constexpr int kProducers = 4;      // wavefronts that build the panel fragments
 constexpr int kTilesPerWave = 4;   // 32-row tiles per consumer wavefront
 constexpr int kDecodeRows = kConsumers * kTilesPerWave * kTileRows;   // rows per workgroup (1024)
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
-// outstanding global load of the wavefront (its fence covers all address spaces), which
-// would drain the consumers' sign window at every block boundary.
-__device__ __forceinline__ void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
 __device__ __forceinline__ float wave_max(float v) {
     for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
     return v;

@@ -55,5 +55,14 @@ __device__ __forceinline__ void store_y(const KParams& p, size_t idx, float v) {
         static_cast<__half*>(p.y)[idx] = __float2half_rn(v);
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load of the wavefront (its fence covers all address spaces), which
+// would drain loads that were issued ahead on purpose (the decode kernel's sign window, the
+// batch kernel's next-block inputs).
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 }  // namespace bitstack

@@ -7,17 +7,18 @@
 // element and is then reused by every token of the tile (the paper's own fused restore-and-
 // multiply variant, its "level 5", pays the same redundant restoration once per token tile).
 //
-// One workgroup (4 wavefronts) owns 64 output rows x TN tokens and walks the input columns in
-// chunks of 256 (one sign unit per 32 rows):
-//   1. x/s for the chunk goes to LDS as fp16, token-major;
-//   2. for every loaded block: V's chunk is transposed into LDS (column-major ranks), the
-//      magnitude tile (U V^T)^T is formed 32 columns x 32 rows at a time with
-//      v_mfma_f32_32x32x16_f16 (K = the 16 ranks) so that a lane holds, for one output row, 16
-//      columns that all live in one 32-bit sign word of that row; the sign is applied as
-//      "add where the bit is set" (bit-field extract, and, add) and S = 2B - 1 is undone at the
-//      end with the plain sum of the magnitude tiles, accumulated for free by the matrix cores;
-//   3. the fp16 weight tile (64 x 256) goes to LDS and meets the activation tile on the matrix
-//      cores (fp32 accumulate).
+// One workgroup (4 wavefronts) owns 64 output rows x up to 512 tokens and walks the input columns
+// in chunks of 256 (one sign unit per 32 rows):
+//   1. for every loaded block: V's chunk is transposed into LDS (column-major ranks), the
+//      tile (U V^T)^T is formed 32 columns x 32 rows at a time with v_mfma_f32_32x32x16_f16
+//      (K = the 16 ranks) so that a lane holds, for one output row, 16 columns that all live in
+//      one 32-bit sign word of that row; the sign enters as a +-1.0 multiplier built from the bit
+//      (bit-field extract, and-or, fused multiply-add).  The block's V values, sign words and U
+//      row are fetched one block ahead of their use;
+//   2. the fp16 weight tile (64 x 256) goes to LDS;
+//   3. per tile of 128 tokens: x/s for the chunk goes to LDS as fp16, token-major, and meets the
+//      weight tile on the matrix cores (fp32 accumulate).  The weight tile is built once per
+//      chunk for all token tiles of the workgroup.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -33,11 +34,20 @@ typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 constexpr int kPanelRows = 64;        // output rows per workgroup
 constexpr int kPanelLd = 264;         // fp16 elements per LDS row of a 256-column tile (+8: bank spread)
 
-template <int TN>
+// A V chunk (256 columns x 16 ranks) in LDS, kept in the order it has in memory: 16 panel positions
+// (t, g) x 16 ranks, one row of 16 columns (32 B) each.  Rows are spaced 48 B and positions 784 B so
+// that both the 128-bit row writes and the 16-bit gathers "one column, 8 ranks" spread over all banks.
+constexpr int kFusedMaxBatch = 64;    // above this the weight-tile kernel is used
+constexpr int kVRow = 48;
+constexpr int kVPos = 16 * kVRow + 16;
+constexpr int kVBuf = 16 * kVPos;
+
+// TT token tiles of 128 tokens per workgroup: the weight tile is rebuilt once per column chunk
+// and reused for all of them (accumulators: 32 registers per tile and lane).
+template <int TT>
 __global__ __launch_bounds__(256) void k_panel(KParams p) {
-    constexpr int TG = TN / 32;       // token groups of 32
-    constexpr int TGW = TG / 2;       // token groups per wavefront in the GEMM stage
-    static_assert(TN == 64 || TN == 128, "token tile");
+    constexpr int TN = 128;           // tokens per activation tile in LDS
+    constexpr int TGW = 2;            // 32-token groups per wavefront and tile in the GEMM stage
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     _Float16* xt = reinterpret_cast<_Float16*>(smem);                                    // [TN][kPanelLd]
     _Float16* wt = xt + TN * kPanelLd;                                                   // [64][kPanelLd]
@@ -46,72 +56,68 @@ __global__ __launch_bounds__(256) void k_panel(KParams p) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hl = lane >> 5, ln = lane & 31;
     const int row_tile0 = blockIdx.x * kPanelRows;
-    const int tok0 = blockIdx.y * TN;
+    const int tok_base = blockIdx.y * (TN * TT);
     const int nch = p.in / kChunkCols;
 
     // reconstruction role of this wavefront: 32 rows x 128 columns of the 64 x 256 tile
     const int rg = wave & 1, chalf = wave >> 1;
     const int rrow = row_tile0 + rg * 32 + ln;             // my output row while reconstructing
-    const bool rrow_ok = rrow < p.out;
-    const int rrow_c = rrow_ok ? rrow : p.out - 1;         // clamped for loads
+    const int rrow_c = rrow < p.out ? rrow : p.out - 1;    // clamped for loads
 
-    // GEMM role: row group rg, token groups chalf, chalf + 2, ...
-    v16f yacc[TGW];
+    // GEMM role: row group rg, token groups chalf and chalf + 2 of every token tile
+    v16f yacc[TT][TGW];
 #pragma unroll
-    for (int k = 0; k < TGW; ++k)
+    for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) yacc[k][v] = 0.0f;
+        for (int k = 0; k < TGW; ++k)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) yacc[tt][k][v] = 0.0f;
+
+    // per-block inputs of the reconstruction, fetched one block ahead
+    struct BlockIn {
+        uint4 va, vb;   // my 16 V values (one panel position, one rank)
+        uint4 sw;       // my row's four sign words of this column half
+        v8h uf;         // my row's U, ranks 8*hl .. 8*hl+7
+    };
+    auto fetch = [&](int i, int ch) -> BlockIn {
+        BlockIn b;
+        const unsigned char* blk = p.blocks + size_t(min(i, p.n_loaded - 1)) * p.block_stride;
+        const uint4* vsrc = reinterpret_cast<const uint4*>(reinterpret_cast<const __half*>(blk + p.off_v) +
+                                                           size_t(ch) * 4096 + tid * 16);
+        b.va = vsrc[0];
+        b.vb = vsrc[1];
+        b.sw = *reinterpret_cast<const uint4*>(blk + (size_t(rrow_c >> 5) * nch + ch) * kUnitBytes +
+                                               (chalf * 32 + (rrow_c & 31)) * 16);
+        b.uf = *reinterpret_cast<const v8h*>(blk + p.off_u + size_t(rrow_c) * 32 + hl * 16);
+        return b;
+    };
 
     for (int ch = 0; ch < nch; ++ch) {
-        // ---- 1. activation tile x/s -> LDS (fp16, token-major)
-        for (int idx = tid; idx < TN * 32; idx += 256) {   // 8 columns per item
-            const int t = idx >> 5, c8 = (idx & 31) * 8;
-            v8h o;
-            if (tok0 + t < p.batch) {
-                const uint4 raw = *reinterpret_cast<const uint4*>(p.x + size_t(tok0 + t) * p.in + ch * kChunkCols + c8);
-                const __half* h = reinterpret_cast<const __half*>(&raw);
-                const float4 r0 = *reinterpret_cast<const float4*>(p.rs + ch * kChunkCols + c8);
-                const float4 r1 = *reinterpret_cast<const float4*>(p.rs + ch * kChunkCols + c8 + 4);
-                const float rr[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
-#pragma unroll
-                for (int k = 0; k < 8; ++k) o[k] = _Float16(__half2float(h[k]) * rr[k]);
-            } else {
-#pragma unroll
-                for (int k = 0; k < 8; ++k) o[k] = _Float16(0.0f);
-            }
-            *reinterpret_cast<v8h*>(xt + t * kPanelLd + c8) = o;
-        }
-
-        // ---- 2. weight tile: sum over blocks of sign (.) (U V^T), 32 rows x 128 columns per wave
-        v16f acc2[4], msum[4];
+        // ---- weight tile: sum over blocks of sign (.) (U V^T), 32 rows x 128 columns per wave
+        v16f acc2[4];
 #pragma unroll
         for (int w4 = 0; w4 < 4; ++w4)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc2[w4][v] = msum[w4][v] = 0.0f;
+            for (int v = 0; v < 16; ++v) acc2[w4][v] = 0.0f;
 
+        BlockIn cur = fetch(0, ch);
         for (int i = 0; i < p.n_loaded; ++i) {
-            const unsigned char* blk = p.blocks + size_t(i) * p.block_stride;
+            const BlockIn nxt = fetch(i + 1, ch);   // clamped: the last one is fetched twice
             // V chunk (256 columns x 16 ranks) -> LDS, column-major ranks
             {
-                const __half* vsrc = reinterpret_cast<const __half*>(blk + p.off_v) + size_t(ch) * 4096 + tid * 16;
-                const uint4 a = reinterpret_cast<const uint4*>(vsrc)[0], b = reinterpret_cast<const uint4*>(vsrc)[1];
-                const unsigned vw[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+                const unsigned vw[8] = {cur.va.x, cur.va.y, cur.va.z, cur.va.w, cur.vb.x, cur.vb.y, cur.vb.z, cur.vb.w};
                 const int pos = tid >> 4, r = tid & 15;
                 const int g = pos & 1, t = pos >> 1;
-                _Float16* dst = vt + (i & 1) * 4096 + r;
+                unsigned short* dst = reinterpret_cast<unsigned short*>(vt + (i & 1) * 4096 + r);
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int col = g * 128 + (e >> 2) * 32 + (e & 3) * 8 + t;
-                    const unsigned short bits = (e & 1) ? (vw[e >> 1] >> 16) : (vw[e >> 1] & 0xFFFFu);
-                    reinterpret_cast<unsigned short*>(dst)[col * 16] = bits;
+                    dst[col * 16] = (e & 1) ? (unsigned short)(vw[e >> 1] >> 16) : (unsigned short)(vw[e >> 1] & 0xFFFFu);
                 }
             }
-            // my row's sign words for this column half, my row's U (ranks 8*hl .. 8*hl+7)
-            const uint4 sw = *reinterpret_cast<const uint4*>(
-                blk + (size_t(rrow_c >> 5) * nch + ch) * kUnitBytes + (chalf * 32 + (rrow_c & 31)) * 16);
-            const unsigned words[4] = {sw.x, sw.y, sw.z, sw.w};
-            const v8h uf = *reinterpret_cast<const v8h*>(blk + p.off_u + size_t(rrow_c) * 32 + hl * 16);
-            __syncthreads();   // V chunk of block i is in LDS (buffer i & 1)
+            const unsigned words[4] = {cur.sw.x, cur.sw.y, cur.sw.z, cur.sw.w};
+            const v8h uf = cur.uf;
+            lds_barrier();     // V chunk of block i is in LDS (buffer i & 1); next block's loads stay in flight
             const _Float16* vb = vt + (i & 1) * 4096;
 #pragma unroll
             for (int w4 = 0; w4 < 4; ++w4) {
@@ -122,77 +128,413 @@ __global__ __launch_bounds__(256) void k_panel(KParams p) {
                 for (int v = 0; v < 16; ++v) z[v] = 0.0f;
                 // C[i = column][n = row]: lane (row ln), register v holds column 8*(v/4) + 4*hl + v%4
                 const v16f m = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, uf, z, 0, 0, 0);
-                msum[w4] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, uf, msum[w4], 0, 0, 0);
-                const int wrd = int(words[w4]);
+                // one shift puts my 16 columns' bits at 8*(v/4) + v%4 for both lane halves;
+                // inverted, so that a set bit marks a negative sign
+                const int wrd = int(~words[w4] >> (4 * hl));
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int bit = 8 * (v >> 2) + 4 * hl + (v & 3);
-                    // all-ones where the sign bit is set (+1), zero otherwise
-                    const int mask = (hl == 0) ? __builtin_amdgcn_sbfe(wrd, 8 * (v >> 2) + (v & 3), 1)
-                                               : __builtin_amdgcn_sbfe(wrd, 8 * (v >> 2) + 4 + (v & 3), 1);
-                    (void)bit;
-                    acc2[w4][v] += __int_as_float(__float_as_int(m[v]) & mask);
+                    const int neg = __builtin_amdgcn_sbfe(wrd, 8 * (v >> 2) + (v & 3), 1);   // all-ones or zero
+                    const float sgn = __int_as_float((neg & int(0x80000000u)) | 0x3f800000);   // -1.0f or +1.0f
+                    acc2[w4][v] = __builtin_fmaf(m[v], sgn, acc2[w4][v]);
                 }
             }
+            cur = nxt;
         }
-        // W' = 2 * (sum over set bits) - (sum of all magnitude tiles) -> fp16 tile in LDS
-        __syncthreads();       // previous chunk's GEMM has finished reading wt
+        // W' tile -> fp16 in LDS
 #pragma unroll
         for (int w4 = 0; w4 < 4; ++w4)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int col = chalf * 128 + w4 * 32 + 8 * (v >> 2) + 4 * hl + (v & 3);
-                wt[(rg * 32 + ln) * kPanelLd + col] = _Float16(2.0f * acc2[w4][v] - msum[w4][v]);
+                wt[(rg * 32 + ln) * kPanelLd + col] = _Float16(acc2[w4][v]);
             }
-        __syncthreads();       // xt and wt complete
 
-        // ---- 3. Y tile += W' tile (64 x 256) * X'^T (256 x TN)
+        // ---- token tiles: x/s -> LDS, then Y tile += W' tile (64 x 256) * X'^T (256 x 128)
 #pragma unroll
-        for (int ks = 0; ks < 16; ++ks) {
-            const v8h af = *reinterpret_cast<const v8h*>(wt + (rg * 32 + ln) * kPanelLd + ks * 16 + hl * 8);
+        for (int tt = 0; tt < TT; ++tt) {
+            const int tok0 = tok_base + tt * TN;
+            if (tok0 < p.batch) {          // uniform over the workgroup
+                for (int idx = tid; idx < TN * 32; idx += 256) {   // 8 columns per item
+                    const int t = idx >> 5, c8 = (idx & 31) * 8;
+                    v8h o;
+                    if (tok0 + t < p.batch) {
+                        const uint4 raw =
+                            *reinterpret_cast<const uint4*>(p.x + size_t(tok0 + t) * p.in + ch * kChunkCols + c8);
+                        const __half* h = reinterpret_cast<const __half*>(&raw);
+                        const float4 r0 = *reinterpret_cast<const float4*>(p.rs + ch * kChunkCols + c8);
+                        const float4 r1 = *reinterpret_cast<const float4*>(p.rs + ch * kChunkCols + c8 + 4);
+                        const float rr[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
 #pragma unroll
-            for (int k = 0; k < TGW; ++k) {
-                const int tg = chalf + 2 * k;
-                const v8h bf = *reinterpret_cast<const v8h*>(xt + (tg * 32 + ln) * kPanelLd + ks * 16 + hl * 8);
-                yacc[k] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf, yacc[k], 0, 0, 0);
+                        for (int k = 0; k < 8; ++k) o[k] = _Float16(__half2float(h[k]) * rr[k]);
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < 8; ++k) o[k] = _Float16(0.0f);
+                    }
+                    *reinterpret_cast<v8h*>(xt + t * kPanelLd + c8) = o;
+                }
+                __syncthreads();       // xt (and, first time round, wt) complete
+#pragma unroll
+                for (int ks = 0; ks < 16; ++ks) {
+                    const v8h af = *reinterpret_cast<const v8h*>(wt + (rg * 32 + ln) * kPanelLd + ks * 16 + hl * 8);
+#pragma unroll
+                    for (int k = 0; k < TGW; ++k) {
+                        const int tg = chalf + 2 * k;
+                        const v8h bf = *reinterpret_cast<const v8h*>(xt + (tg * 32 + ln) * kPanelLd + ks * 16 + hl * 8);
+                        yacc[tt][k] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf, yacc[tt][k], 0, 0, 0);
+                    }
+                }
+                __syncthreads();       // xt free for the next tile, wt for the next chunk
             }
         }
-        __syncthreads();       // xt, wt free for the next chunk
     }
 
     // ---- store: C[i = row][n = token]: lane (token ln), register v holds row 8*(v/4) + 4*hl + v%4
 #pragma unroll
-    for (int k = 0; k < TGW; ++k) {
-        const int tok = tok0 + (chalf + 2 * k) * 32 + ln;
-        if (tok < p.batch) {
+    for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = row_tile0 + rg * 32 + 8 * (v >> 2) + 4 * hl + (v & 3);
-                if (row < p.out) store_y(p, size_t(tok) * p.out + row, yacc[k][v]);
+        for (int k = 0; k < TGW; ++k) {
+            const int tok = tok_base + tt * TN + (chalf + 2 * k) * 32 + ln;
+            if (tok < p.batch) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row_tile0 + rg * 32 + 8 * (v >> 2) + 4 * hl + (v & 3);
+                    if (row < p.out) store_y(p, size_t(tok) * p.out + row, yacc[tt][k][v]);
+                }
             }
         }
-    }
 }
 
-template <int TN>
+template <int TT>
 static hipError_t launch_panel_t(const KParams& p, hipStream_t st) {
-    const size_t smem = size_t(TN + kPanelRows) * kPanelLd * 2 + 2 * 4096 * 2;
+    const size_t smem = size_t(128 + kPanelRows) * kPanelLd * 2 + 2 * 4096 * 2;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_panel<TN>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_panel<TT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(smem));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((p.out + kPanelRows - 1) / kPanelRows, (p.batch + TN - 1) / TN);
-    hipLaunchKernelGGL((k_panel<TN>), grid, dim3(256), smem, st, p);
+    dim3 grid((p.out + kPanelRows - 1) / kPanelRows, (p.batch + 128 * TT - 1) / (128 * TT));
+    hipLaunchKernelGGL((k_panel<TT>), grid, dim3(256), smem, st, p);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Small batches (up to 64 tokens): no weight tile is kept at all.  Each block's signed 32 x 32
+// tile goes straight from the accumulator registers of the magnitude product into the B operand
+// of the product with the activations, so the sum over blocks (Eq. 8) happens inside the fp32
+// accumulators of Y on the matrix cores:
+//
+//     Y[t][o] += sum_j X'[t][j] * ( S_i[o][j] * (U_i V_i^T)[o][j] )      for every block i
+//
+// The magnitude product is laid out C[i = column][n = row]: a lane holds one row and 16 columns
+// 8*(v/4) + 4*half + v%4 of the tile, exactly the "K index on registers, N index on lanes" shape
+// of a B operand whose K runs over columns.  Registers v and v + 8 sit 16 columns apart, i.e.
+// 16 bits apart in the row's sign word, so one shift lines both sign bits up with the sign bits
+// of a packed fp16 pair and one three-input bit operation flips them: 1.5 vector instructions per
+// weight element and block (convert-pack, shift, xor-and).  K slots are permuted the same way in
+// the activation fragments, which are built once per column chunk and stay in registers for all
+// blocks.
+//
+// One workgroup = 64 output rows x 32 tokens; 8 wavefronts = 2 teams (even / odd column chunks)
+// x 4 column quarters of a chunk; every wavefront handles both 32-row groups, so one V fragment
+// and one activation fragment serve two products.  The eight partial Y tiles meet in LDS at the
+// end.  More than 32 tokens: blockIdx.y walks the token groups (the signed tiles are rebuilt per
+// group; the weight-tile kernel above takes over where that stops paying).
+//
+// Nothing in the main loop is shared between wavefronts, so it has no barrier: each wavefront
+// turns its own 64 columns of V from "16 columns of one rank" rows into "8 ranks of one column"
+// fragments through a private piece of LDS (LDS operations of one wavefront execute in order), and
+// keeps its own 64 columns of x/s there.  The U rows of all loaded blocks (2 KiB per block) are
+// cached in LDS once.
+//
+// A step is one (column chunk, block) pair of a team, chunks outermost.  Inputs travel three
+// steps deep and are never copied between registers while in flight (a copy would wait for the
+// load): three named register sets rotate through a loop unrolled three times.
+//   step s:  V(s+1) registers -> LDS -> V(s+1) fragments | compute block s from signs(s), U(s),
+//            fragments(s) | issue loads of signs(s+2), V(s+3)
+constexpr int kVtStride = 68;                       // dwords between panel positions t in the private V piece
+constexpr int kVPriv = 8 * kVtStride * 4;           // bytes per private V buffer (8 t x 16 ranks x 8 columns)
+constexpr int kXPrivLd = 72;                        // fp16 per token row of the private x/s piece (64 + 8)
+constexpr int kXPriv = 32 * kXPrivLd * 2;           // bytes
+constexpr int kFusedFixedLds = 8 * (2 * kVPriv + kXPriv);
+constexpr int kFusedMaxBlocks = (160 * 1024 - kFusedFixedLds) / 2048 - 1;   // U cache: 2 KiB per block
+
+__global__ __launch_bounds__(512) void k_fused(KParams p) {
+    constexpr int XPT = 4;   // tokens per lane when staging activations
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int team = wave >> 2, cw = wave & 3;
+    const int hl = lane >> 5, ln = lane & 31;
+    unsigned char* const vpriv = smem + wave * (2 * kVPriv + kXPriv);
+    _Float16* const xpriv = reinterpret_cast<_Float16*>(vpriv + 2 * kVPriv);
+    unsigned char* const ucache = smem + kFusedFixedLds;   // [block][64 rows][32 B]
+    const int nch = p.in / kChunkCols;
+    const int iters = (nch + 1) / 2;
+    const int n = p.n_loaded;
+    const int total = iters * n;
+    const int rt0 = blockIdx.x * 2, nrt = p.out / kTileRows;
+    const int rtc[2] = {min(rt0, nrt - 1), min(rt0 + 1, nrt - 1)};   // clamped for loads
+    const int tok0 = blockIdx.y * 32;
+
+    // ---- U rows of my 64 output rows, all blocks -> LDS
+    for (int idx = tid; idx < n * 128; idx += 512) {
+        const int i = idx >> 7, piece = idx & 127;         // 16-byte pieces: row = piece / 2
+        const int row = rtc[piece >> 6] * kTileRows + ((piece >> 1) & 31);
+        *reinterpret_cast<uint4*>(ucache + idx * 16) = *reinterpret_cast<const uint4*>(
+            p.blocks + size_t(i) * p.block_stride + p.off_u + size_t(row) * 32 + (piece & 1) * 16);
+    }
+
+    // ---- activations: x/s of my 64 columns of one chunk as fp16 in my LDS piece, token-major
+    struct XIn {
+        uint4 x[XPT];
+        float4 r0, r1;
+    };
+    const int cg = lane & 7, tl = lane >> 3;   // staging role: 8 columns, tokens tl, tl + 8, ...
+    auto fetch_x = [&](int it) -> XIn {         // chunk of my team's iteration `it`, clamped
+        XIn v;
+        const int col = min(2 * it + team, nch - 1) * kChunkCols + cw * 64 + cg * 8;
+#pragma unroll
+        for (int m = 0; m < XPT; ++m)
+            v.x[m] = *reinterpret_cast<const uint4*>(p.x + size_t(min(tok0 + tl + 8 * m, p.batch - 1)) * p.in + col);
+        v.r0 = *reinterpret_cast<const float4*>(p.rs + col);
+        v.r1 = *reinterpret_cast<const float4*>(p.rs + col + 4);
+        return v;
+    };
+    auto store_x = [&](XIn v, int it) {         // a team without a chunk left (odd chunk count) gets zeros
+        const float rr[8] = {v.r0.x, v.r0.y, v.r0.z, v.r0.w, v.r1.x, v.r1.y, v.r1.z, v.r1.w};
+        const bool valid = 2 * it + team < nch;
+#pragma unroll
+        for (int m = 0; m < XPT; ++m) {
+            const int tok = tl + 8 * m;
+            const float on = (valid && tok0 + tok < p.batch) ? 1.0f : 0.0f;
+            const __half* h = reinterpret_cast<const __half*>(&v.x[m]);
+            v8h o;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) o[k] = _Float16(__half2float(h[k]) * rr[k] * on);
+            *reinterpret_cast<v8h*>(xpriv + tok * kXPrivLd + cg * 8) = o;
+        }
+    };
+    // activation fragments, K slots in the order the signed tile has them:
+    // slot 2p <-> column 8*mf + 4*hl + p, slot 2p + 1 <-> that + 16
+    v8h afr[2][2];
+    auto build_afr = [&]() {
+#pragma unroll
+        for (int tile = 0; tile < 2; ++tile)
+#pragma unroll
+            for (int mf = 0; mf < 2; ++mf) {
+                const _Float16* src = xpriv + ln * kXPrivLd + tile * 32 + mf * 8 + 4 * hl;
+                const uint2 lo = *reinterpret_cast<const uint2*>(src);
+                const uint2 hi = *reinterpret_cast<const uint2*>(src + 16);
+                const unsigned w[4] = {(lo.x & 0xFFFFu) | (hi.x << 16), (lo.x >> 16) | (hi.x & 0xFFFF0000u),
+                                       (lo.y & 0xFFFFu) | (hi.y << 16), (lo.y >> 16) | (hi.y & 0xFFFF0000u)};
+                afr[tile][mf] = __builtin_bit_cast(v8h, w);
+            }
+    };
+
+    // ---- per-step inputs
+    struct Pos {
+        int it, i;   // team iteration (chunk), block
+    };
+    auto advance = [&](Pos q) -> Pos {
+        if (++q.i == n) {
+            q.i = 0;
+            ++q.it;
+        }
+        return q;
+    };
+    // past the last step the last chunk is read again, harmlessly
+    auto chunk_of = [&](Pos q) -> int { return min(2 * q.it + team, nch - 1); };
+    auto block_of = [&](Pos q) -> const unsigned char* { return p.blocks + size_t(q.i) * p.block_stride; };
+    // V: my wavefront needs, of every row (t, g, r) with g = my column half, the 8 columns
+    // e = 8*(cw&1) .. +7, i.e. 16 of its 32 bytes; lane L takes rows (t = L/8, r = 2*(L%8) and + 1)
+    struct VIn {
+        uint4 a, b;
+    };
+    const unsigned voff = unsigned((((lane >> 3) * 2 + (cw >> 1)) * 16 + 2 * (lane & 7)) * 32 + (cw & 1) * 16);
+    auto fetch_v = [&](Pos q) -> VIn {
+        const unsigned char* src = block_of(q) + p.off_v + size_t(chunk_of(q)) * 8192;
+        VIn v;
+        v.a = *reinterpret_cast<const uint4*>(src + voff);
+        v.b = *reinterpret_cast<const uint4*>(src + voff + 32);
+        return v;
+    };
+    struct SIn {
+        uint2 w[2];   // per row group: my row's two sign words of my 64 columns
+    };
+    const unsigned soff[2] = {unsigned((size_t(rtc[0]) * nch) * kUnitBytes + ((cw >> 1) * 32 + ln) * 16 + (cw & 1) * 8),
+                              unsigned((size_t(rtc[1]) * nch) * kUnitBytes + ((cw >> 1) * 32 + ln) * 16 + (cw & 1) * 8)};
+    auto fetch_s = [&](Pos q) -> SIn {
+        const unsigned char* src = block_of(q) + size_t(chunk_of(q)) * kUnitBytes;
+        SIn v;
+        v.w[0] = *reinterpret_cast<const uint2*>(src + soff[0]);
+        v.w[1] = *reinterpret_cast<const uint2*>(src + soff[1]);
+        return v;
+    };
+
+    // my private V piece: dword address of (t, r, column pair c2) = t * kVtStride + r * 4 + c2; the
+    // stride of 68 spreads both the 128-bit row writes and the 16-bit fragment gathers over all banks
+    unsigned char* const vdst = vpriv + ((lane >> 3) * kVtStride + 2 * (lane & 7) * 4) * 4;
+    int vsrc_off[2];
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile) {
+        const int b = ln >> 3, t = ln & 7, e = tile * 4 + b;   // e: column of my 8 within a row
+        vsrc_off[tile] = (t * kVtStride + 8 * hl * 4) * 4 + e * 2;
+    }
+    auto stage_v = [&](VIn v, int buf) {
+        *reinterpret_cast<uint4*>(vdst + buf * kVPriv) = v.a;        // rank r
+        *reinterpret_cast<uint4*>(vdst + buf * kVPriv + 16) = v.b;   // rank r + 1
+    };
+    auto read_vf = [&](int buf, int tile) -> v8h {
+        // A operand of the magnitude product: my column's ranks 8*hl .. 8*hl + 7
+        v8h vf;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            vf[k] = *reinterpret_cast<const _Float16*>(vpriv + buf * kVPriv + vsrc_off[tile] + k * 16);
+        return vf;
+    };
+    auto read_u = [&](int i, int rg) -> v8h {   // my row's U, ranks 8*hl .. 8*hl + 7
+        return *reinterpret_cast<const v8h*>(ucache + ((i * 64 + rg * 32 + ln) * 2 + hl) * 16);
+    };
+
+    v16f yacc[2];
+#pragma unroll
+    for (int rg = 0; rg < 2; ++rg)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) yacc[rg][v] = 0.0f;
+
+    auto compute = [&](const SIn& sg, v8h uf0, v8h uf1, v8h vf0, v8h vf1) {
+#pragma unroll
+        for (int tile = 0; tile < 2; ++tile) {
+            const v8h vf = tile ? vf1 : vf0;
+#pragma unroll
+            for (int rg = 0; rg < 2; ++rg) {
+                v16f z;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                // C[i = column][n = row]: lane (row ln), register v holds column 8*(v/4) + 4*hl + v%4
+                const v16f m = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, rg ? uf1 : uf0, z, 0, 0, 0);
+                // inverted, so that a set bit marks a negative sign; bit of register v at 8*(v/4) + v%4
+                const unsigned wrd = ~(tile ? sg.w[rg].y : sg.w[rg].x) >> (4 * hl);
+#pragma unroll
+                for (int mf = 0; mf < 2; ++mf) {
+                    unsigned r4[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+                        h2 c;
+                        c[0] = _Float16(m[4 * mf + k]);
+                        c[1] = _Float16(m[4 * mf + k + 8]);
+                        // sign bits of the pair: word bits 8*mf + k and 16 + 8*mf + k -> bits 15 and 31
+                        const unsigned flip = (wrd << (15 - 8 * mf - k)) & 0x80008000u;
+                        r4[k] = __builtin_bit_cast(unsigned, c) ^ flip;
+                    }
+                    yacc[rg] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[tile][mf], __builtin_bit_cast(v8h, r4), yacc[rg], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    // ---- prologue: steps 0..2 on their way, chunk 0's activations and V(0) fragments ready
+    Pos q = {0, 0};
+    VIn vA = fetch_v(q);
+    SIn sA = fetch_s(q);
+    q = advance(q);
+    VIn vB = fetch_v(q);
+    SIn sB = fetch_s(q);
+    q = advance(q);          // q: position of step s + 2 (signs)
+    Pos qv = advance(q);     // qv: position of step s + 3 (V)
+    VIn vC = fetch_v(q);
+    SIn sC;
+    store_x(fetch_x(0), 0);
+    stage_v(vA, 0);
+    v8h vf0 = read_vf(0, 0), vf1 = read_vf(0, 1);
+    build_afr();
+    XIn xn = fetch_x(1);
+    __syncthreads();         // U cache complete
+
+    int ci = 0, it = 0;      // block index inside the chunk, team iteration
+    // one step; CUR: set in use, NXT: set whose V goes to LDS now, FAR: set that receives signs(s+2);
+    // V(s+3) lands in CUR's V registers (V(s) left them one step ago)
+#define BS_FUSED_STEP(S, CUR, NXT, FAR)                                                    \
+    {                                                                                      \
+        const v8h uf0 = read_u(ci, 0), uf1 = read_u(ci, 1);                                \
+        stage_v(v##NXT, ((S) + 1) & 1);                                                    \
+        const v8h vn0 = read_vf(((S) + 1) & 1, 0), vn1 = read_vf(((S) + 1) & 1, 1);        \
+        if (ci == 0 && (S) > 0) {                                                          \
+            store_x(xn, it);                                                               \
+            build_afr();                                                                   \
+            xn = fetch_x(it + 1);                                                          \
+        }                                                                                  \
+        s##FAR = fetch_s(q);                                                               \
+        v##CUR = fetch_v(qv);                                                              \
+        q = advance(q);                                                                    \
+        qv = advance(qv);                                                                  \
+        compute(s##CUR, uf0, uf1, vf0, vf1);                                               \
+        vf0 = vn0;                                                                         \
+        vf1 = vn1;                                                                         \
+        if (++ci == n) {                                                                   \
+            ci = 0;                                                                        \
+            ++it;                                                                          \
+        }                                                                                  \
+    }
+    // The step count is rounded up to a multiple of three without branches around the steps (a
+    // branch would make the compiler wait for every load in flight): the extra steps start a new
+    // "chunk" past the last one, whose activations are written as zeros, so they add nothing.
+    for (int s = 0; s < total; s += 3) {
+        BS_FUSED_STEP(s, A, B, C)
+        BS_FUSED_STEP(s + 1, B, C, A)
+        BS_FUSED_STEP(s + 2, C, A, B)
+    }
+#undef BS_FUSED_STEP
+
+    // ---- the eight partial tiles meet in LDS; C[i = token][n = row]: lane (row ln),
+    //      register v holds token 8*(v/4) + 4*hl + v%4 of the group
+    float* red = reinterpret_cast<float*>(smem);   // [8][16][64]
+#pragma unroll
+    for (int rg = 0; rg < 2; ++rg) {
+        __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[(wave * 16 + v) * 64 + lane] = yacc[rg][v];
+        __syncthreads();
+        for (int o = tid; o < 1024; o += 512) {
+            const int v = o >> 6, l = o & 63;
+            float sum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 8; ++w) sum += red[(w * 16 + v) * 64 + l];
+            const int tok = tok0 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
+            const int row = (rt0 + rg) * kTileRows + (l & 31);
+            if (tok < p.batch && row < p.out) store_y(p, size_t(tok) * p.out + row, sum);
+        }
+    }
+}
+
+static bool fused_fits(const KParams& p) { return p.n_loaded <= kFusedMaxBlocks; }
+
+static hipError_t launch_fused(const KParams& p, hipStream_t st) {
+    const size_t smem = size_t(kFusedFixedLds) + size_t(p.n_loaded) * 2048;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fused),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           kFusedFixedLds + kFusedMaxBlocks * 2048);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((p.out + 2 * kTileRows - 1) / (2 * kTileRows), (p.batch + 31) / 32);
+    hipLaunchKernelGGL(k_fused, grid, dim3(512), smem, st, p);
     return hipGetLastError();
 }
 
 hipError_t launch_panel(const LaunchArgs& a, hipStream_t st) {
     KParams p = make_params(a);
-    if (a.batch > 64) return launch_panel_t<128>(p, st);
-    return launch_panel_t<64>(p, st);
+    if (a.n_loaded < 1 || a.batch < 1) return hipErrorInvalidValue;
+    if (a.batch <= kFusedMaxBatch && fused_fits(p)) return launch_fused(p, st);
+    if (a.batch > 256) return launch_panel_t<4>(p, st);
+    if (a.batch > 128) return launch_panel_t<2>(p, st);
+    return launch_panel_t<1>(p, st);
 }
 
 }  // namespace bitstack

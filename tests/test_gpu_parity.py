@@ -129,6 +129,26 @@ def test_small_and_ragged_shapes(B, out, inn, n):
             assert err <= TOL
 
 
+@pytest.mark.parametrize("out,inn,n", [(1056, 768, 3), (96, 2048, 2)])
+def test_batch_kernels_every_tile_variant(B, out, inn, n):
+    """Batch sizes on both sides of every switch inside the batch path: one / two token groups
+    of the small-batch kernel, one / two / four token tiles of the weight-tile kernel, each with
+    a ragged last group, an odd number of column chunks and an odd number of row tiles."""
+    st = synth_stack(3, out, inn, n)
+    batches = (1, 31, 32, 33, 64, 65, 128, 129, 257, 300, 513)
+    ps = _pack(B, st, max_batch=max(batches))
+    x = acts(3, max(batches), inn)
+    ref = O.forward_dense(st, x, n)
+    for b in batches:
+        for nl in (1, n):
+            want = ref[:b] if nl == n else O.forward_dense(st, x[:b], nl)
+            y = _run(B, ps, x[:b], nl, B.KERNEL_PANEL)
+            assert y.shape == (b, out)
+            err = O.relative_error(y, want)
+            print(f"{out}x{inn} batch kernel B={b} n_loaded={nl}: {err:.2e}", flush=True)
+            assert err <= TOL
+
+
 def test_argument_errors_on_device(B):
     import torch
     st = synth_stack(3, 32, 256, 1)
