@@ -132,9 +132,13 @@ int bitstack_linear(const void* x, const bitstack_weight_t* blocks, int n_loaded
 /* A sequence of batch-1 forward passes enqueued back to back on one stream from
  * native code (one token through many linears, e.g. the 224 linears of a decoder,
  * each with its own n_loaded as the sorted stack leaves them, Section 2.2).
- * Equivalent to calling bitstack_linear(jobs[i].x, jobs[i].blocks, jobs[i].n_loaded,
+ * Same results as calling bitstack_linear(jobs[i].x, jobs[i].blocks, jobs[i].n_loaded,
  * jobs[i].y, stream) for i = 0..count-1, the whole list `repeat` times.
- * Stops at the first failing job and returns its error. */
+ * Up to four consecutive jobs that read the same x (the q/k/v or the gate/up projections
+ * of a decoder layer) are independent of each other and are merged into one kernel
+ * launch, provided they use different stacks, their outputs overlap neither each other
+ * nor x, and the stacks' input widths agree; such jobs then run concurrently, not in
+ * list order.  Stops at the first failing job or launch and returns its error. */
 typedef struct bitstack_job {
     const void* x;                   /* device fp16 [in]  */
     const bitstack_weight_t* blocks; /* packed stack      */

@@ -10,6 +10,7 @@
 
 #include "../../include/bitstack.h"
 #include "kernels.h"
+#include "kparams.h"
 #include "layout.h"
 
 using namespace bitstack;
@@ -291,14 +292,63 @@ int bitstack_set_option(int option, int value) {
     }
 }
 
+// can job j ride in the same decode launch as the jobs [first, j) before it?  Same input
+// vector, same slab width, a non-empty stack, and no output of the group overlapping the input
+// (jobs of one launch run concurrently).
+static bool can_join(const bitstack_job_t* jobs, int first, int j) {
+    const bitstack_job_t& a = jobs[first];
+    const bitstack_job_t& b = jobs[j];
+    if (!a.x || !a.blocks || !a.y || !b.x || !b.blocks || !b.y) return false;
+    if (b.x != a.x || b.blocks->geo.in != a.blocks->geo.in) return false;
+    if (b.blocks->geo.min_slab != a.blocks->geo.min_slab) return false;
+    if (b.n_loaded < 1 || b.n_loaded > b.blocks->geo.n || a.n_loaded < 1 || a.n_loaded > a.blocks->geo.n) return false;
+    if (reinterpret_cast<uintptr_t>(b.x) % 16 || reinterpret_cast<uintptr_t>(b.y) % 16) return false;
+    const char* x0 = static_cast<const char*>(a.x);
+    const char* x1 = x0 + size_t(a.blocks->geo.in) * 2;
+    for (int k = first; k <= j; ++k) {
+        const char* y0 = static_cast<const char*>(jobs[k].y);
+        const char* y1 = y0 + size_t(jobs[k].blocks->geo.out) * 2;
+        if (y0 < x1 && x0 < y1) return false;
+        for (int m = first; m < k; ++m) {   // two jobs of a launch must not share a stack (its workspace) or an output
+            if (jobs[m].blocks == jobs[k].blocks) return false;
+            const char* z0 = static_cast<const char*>(jobs[m].y);
+            const char* z1 = z0 + size_t(jobs[m].blocks->geo.out) * 2;
+            if (y0 < z1 && z0 < y1) return false;
+        }
+    }
+    return true;
+}
+
 int bitstack_linear_many(const bitstack_job_t* jobs, int count, int repeat, bitstack_stream_t stream) {
     if (!jobs) return BITSTACK_E_NULL;
     if (count < 0 || repeat < 0) return BITSTACK_E_RANGE;
-    for (int r = 0; r < repeat; ++r)
-        for (int i = 0; i < count; ++i) {
-            int rc = bitstack_linear(jobs[i].x, jobs[i].blocks, jobs[i].n_loaded, jobs[i].y, stream);
-            if (rc) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    for (int r = 0; r < repeat; ++r) {
+        int i = 0;
+        while (i < count) {
+            int len = 1;
+            while (i + len < count && len < kMaxGroup && can_join(jobs, i, i + len)) ++len;
+            if (len > 1) {
+                LaunchArgs a[kMaxGroup];
+                for (int k = 0; k < len; ++k) {
+                    const bitstack_job_t& jb = jobs[i + k];
+                    a[k].x = jb.x;
+                    a[k].y = jb.y;
+                    a[k].image = jb.blocks->dev;
+                    a[k].geo = jb.blocks->geo;
+                    a[k].batch = 1;
+                    a[k].n_loaded = jb.n_loaded;
+                    a[k].y_f32 = false;
+                }
+                hipError_t e = launch_decode_group(a, len, st);
+                if (e != hipSuccess) return hip_fail(e);
+            } else {
+                int rc = bitstack_linear(jobs[i].x, jobs[i].blocks, jobs[i].n_loaded, jobs[i].y, stream);
+                if (rc) return rc;
+            }
+            i += len;
         }
+    }
     return BITSTACK_OK;
 }
 

@@ -27,6 +27,8 @@ hipError_t launch_stream_read(const void* buf, size_t bytes, void* sink, int blo
 hipError_t launch_zero(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_reference(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_decode(const LaunchArgs& a, hipStream_t st);
+// up to 4 batch-1 calls in one launch; all must use the same column slab (Geometry::min_slab)
+hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st);
 hipError_t launch_panel(const LaunchArgs& a, hipStream_t st);
 
 }  // namespace bitstack

@@ -169,6 +169,7 @@ hipError_t launch_reference(const LaunchArgs& a, hipStream_t st) {
 // ---------------------------------------------------------------- decode kernel
 constexpr float kQMax = 32512.0f;  // |q| <= 127*256: the high byte stays in int8 after +128 rounding
 constexpr int kMaxBlocksPerWg = 32;
+constexpr int kMaxPre = 8;           // blocks per workgroup whose slab maxima are ready at the first barrier
 constexpr int kConsumers = 8;      // wavefronts that stream signs through the matrix cores
 constexpr int kProducers = 4;      // wavefronts that build the panel fragments
 constexpr int kTilesPerWave = 4;   // 32-row tiles per consumer wavefront
@@ -197,7 +198,7 @@ __device__ __forceinline__ float wave_max(float v) {
 // One barrier per block separates "fragments of block q+1 written" from "fragments of
 // block q read".
 template <int KS>
-__global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KParams p) {
+__global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KGroup grp) {
     constexpr int NCH = KS / kChunkCols;   // sign chunks per slab
     constexpr int R = kTilesPerWave;       // 32-row tiles per consumer wavefront
     constexpr int RS = kDecodeRows;
@@ -220,12 +221,17 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
     const bool producer = wave >= kConsumers;
     const int ptid = tid - kConsumers * 64;   // producer thread index (valid when producer)
 
+    // which stack of the group this workgroup serves (uniform)
+    int gi = 0;
+    while (gi + 1 < grp.count && blockIdx.x >= grp.base[gi + 1]) ++gi;
+    const KParams& p = grp.s[gi];
     // workgroup id -> work item, contiguous ranges of items per XCD (ids are dealt
-    // round-robin to the 8 XCDs), so that the workgroups sharing a V slab share an L2
-    const unsigned total = gridDim.x;
-    const unsigned xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
-    const unsigned q8 = total >> 3, rem = total & 7u;
-    const unsigned item = xcd * q8 + min(xcd, rem) + slot;
+    // round-robin to the 8 XCDs), so that the workgroups sharing a V slab share an L2.
+    // The id range of a stack is padded to a multiple of 8; ids past the last item leave.
+    const unsigned local = blockIdx.x - grp.base[gi];
+    const unsigned q8 = (grp.base[gi + 1] - grp.base[gi]) >> 3;
+    const unsigned item = (local & 7u) * q8 + (local >> 3);
+    if (item >= unsigned(p.n_rs) * unsigned(p.n_ks) * unsigned(p.n_bg)) return;
     const int rs_i = item % p.n_rs;
     const int ks_i = (item / p.n_rs) % p.n_ks;
     const int bg_i = item / (p.n_rs * p.n_ks);
@@ -248,8 +254,9 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
     };
 
     BS_TRACE(0);
-    // Both roles pass the same barriers: P1 (x/s slab in LDS), P2 (per-block maxima in
-    // LDS), P3 (block 0 staged), then one per block.
+    // Both roles pass the same barriers: P1 (x/s slab and the first blocks' maxima in LDS), P2
+    // (remaining maxima; only if the workgroup has more than kMaxPre blocks), P3 (block 0
+    // staged), then one per block.
     if (producer) {
         // ============================================================== producers
         // one producer wave shares a SIMD with two consumer waves that are almost never
@@ -379,7 +386,7 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
         // ---- activation slab x/s in panel order (once per workgroup); the per-channel
         // maxima of my first blocks and block 0's raw data are requested at the same time
         if (ptid < 96) cs[ptid] = 0;
-        constexpr int NPRE = 8;   // blocks whose maxima are fetched before the first barrier
+        constexpr int NPRE = kMaxPre;   // blocks whose maxima are fetched before the first barrier
         struct alignas(XP * 2) HVec {
             __half h[XP];
         };
@@ -401,38 +408,43 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
         }
         Raw ra = load_raw(0);
         const URows u0 = load_u(0);
-#pragma unroll
-        for (int m = 0; m < XP; ++m) xs[ptid * XP + m] = xv[m] * rv[m];
-        lds_barrier();   // P1
-        BS_TRACE(1);
         // ---- exact max |V[j][r] * xs[j]| over the slab for each of my blocks:
-        //      max_j |xs[j]| * max_r |V[j][r]|, the inner maximum stored at pack time
-        {
-            float xa[XP];
+        //      max_j |xs[j]| * max_r |V[j][r]|, the inner maximum stored at pack time.
+        //      The first NPRE blocks are done from registers before the first barrier.
+        float xa[XP];
 #pragma unroll
-            for (int m = 0; m < XP; ++m) xa[m] = fabsf(xs[ptid * XP + m]);
-            for (int qb = 0; qb < nb; qb += NPRE) {
-                if (qb > 0) {
+        for (int m = 0; m < XP; ++m) {
+            const float v = xv[m] * rv[m];
+            xs[ptid * XP + m] = v;
+            xa[m] = fabsf(v);
+        }
+        auto slab_max = [&](int qb) {
 #pragma unroll
-                    for (int k = 0; k < NPRE; ++k) {
-                        const __half* vm = p.vmax + size_t(block_index(min(qb + k, nb - 1))) * p.in +
-                                           size_t(c0) * kChunkCols + ptid * XP;
-                        hv[k] = *reinterpret_cast<const HVec*>(vm);
-                    }
-                }
+            for (int k = 0; k < NPRE; ++k) {
+                if (qb + k < nb) {
+                    float a = 0.0f;
 #pragma unroll
-                for (int k = 0; k < NPRE; ++k) {
-                    if (qb + k < nb) {
-                        float a = 0.0f;
-#pragma unroll
-                        for (int m = 0; m < XP; ++m) a = fmaxf(a, xa[m] * __half2float(hv[k].h[m]));
-                        a = wave_max(a);
-                        if (lane == 0) amax_w[(wave - kConsumers) * kMaxBlocksPerWg + qb + k] = a;
-                    }
+                    for (int m = 0; m < XP; ++m) a = fmaxf(a, xa[m] * __half2float(hv[k].h[m]));
+                    a = wave_max(a);
+                    if (lane == 0) amax_w[(wave - kConsumers) * kMaxBlocksPerWg + qb + k] = a;
                 }
             }
+        };
+        slab_max(0);
+        lds_barrier();   // P1
+        BS_TRACE(1);
+        if (nb > NPRE) {   // same for the whole workgroup
+            for (int qb = NPRE; qb < nb; qb += NPRE) {
+#pragma unroll
+                for (int k = 0; k < NPRE; ++k) {
+                    const __half* vm = p.vmax + size_t(block_index(min(qb + k, nb - 1))) * p.in +
+                                       size_t(c0) * kChunkCols + ptid * XP;
+                    hv[k] = *reinterpret_cast<const HVec*>(vm);
+                }
+                slab_max(qb);
+            }
+            lds_barrier();   // P2
         }
-        lds_barrier();   // P2
         BS_TRACE(2);
         Raw rb = load_raw(1);
         quantise(0, ra);
@@ -568,7 +580,7 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
 #pragma unroll
             for (int tl = 0; tl < R; ++tl)
                 win[c][tl] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, unit_off(0, tl) + c * kUnitBytes, 0, 0);
-        lds_barrier();   // P2
+        if (nb > kMaxPre) lds_barrier();   // P2
         BS_TRACE(2);
         lds_barrier();   // P3
         BS_TRACE(3);
@@ -606,22 +618,50 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
     __syncthreads();
     BS_TRACE(6);
     if (*flag) {
+        // One pass with every load in flight at once: thread = (4 consecutive rows, a third of
+        // the slots), 128-bit loads; the three partial sums meet in LDS.  Fixed summation order,
+        // so the result does not depend on which workgroup arrived last.  The acquire makes this
+        // compute unit's caches drop what they hold of the workspace (rows written during an
+        // earlier call may still sit in this XCD's L2); the loads after it are ordinary ones.
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        static_assert(NT == 768 && RS == 1024, "finisher mapping: 256 row quads x 3 slot groups");
         const int nslots = p.n_ks * p.n_bg;
-        for (int i = tid; i < RS && row0 + i < p.out; i += NT) {
-            const float* src = p.part + row0 + i;
-            float tot = 0.0f;
-            for (int sl = 0; sl < nslots; sl += 64) {   // 64 loads in flight, fixed summation order
-                float v[64];
+        const int rq = tid & 255, sg = tid >> 8;
+        const int row = row0 + 4 * rq;
+        const bool live = row < p.out;   // out is a multiple of 32: a quad is inside or outside as a whole
+        float4 tot = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (live) {
+            const float* src = p.part + row;
+            constexpr int MAXK = 24;     // slots per group and round
+            for (int base = 0; base < nslots; base += 3 * MAXK) {
+                float4 v[MAXK];
 #pragma unroll
-                for (int k = 0; k < 64; ++k)
-                    v[k] = (sl + k < nslots) ? __hip_atomic_load(src + size_t(sl + k) * p.out, __ATOMIC_RELAXED,
-                                                                 __HIP_MEMORY_SCOPE_AGENT)
-                                             : 0.0f;
+                for (int k = 0; k < MAXK; ++k) {
+                    const int sl = base + 3 * k + sg;
+                    v[k] = sl < nslots ? *reinterpret_cast<const float4*>(src + size_t(sl) * p.out)
+                                       : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                }
 #pragma unroll
-                for (int k = 0; k < 64; ++k) tot += v[k];
+                for (int k = 0; k < MAXK; ++k) {
+                    tot.x += v[k].x; tot.y += v[k].y; tot.z += v[k].z; tot.w += v[k].w;
+                }
             }
-            store_y(p, size_t(row0 + i), tot);
+        }
+        float4* red = reinterpret_cast<float4*>(smem);   // [3][256]; fragments are dead by now
+        red[sg * 256 + rq] = tot;
+        __syncthreads();
+        if (sg == 0 && live) {
+            const float4 a = red[rq], b2 = red[256 + rq], c = red[512 + rq];
+            const float o4[4] = {(a.x + b2.x) + c.x, (a.y + b2.y) + c.y, (a.z + b2.z) + c.z, (a.w + b2.w) + c.w};
+            if (p.y_f32) {
+                *reinterpret_cast<float4*>(static_cast<float*>(p.y) + row) = make_float4(o4[0], o4[1], o4[2], o4[3]);
+            } else {
+                __half2 h01 = __floats2half2_rn(o4[0], o4[1]), h23 = __floats2half2_rn(o4[2], o4[3]);
+                uint2 pk;
+                pk.x = *reinterpret_cast<unsigned*>(&h01);
+                pk.y = *reinterpret_cast<unsigned*>(&h23);
+                *reinterpret_cast<uint2*>(static_cast<__half*>(p.y) + row) = pk;
+            }
         }
         if (tid == 0) __hip_atomic_store(&p.ctr[rs_i], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -629,29 +669,40 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KP
 }
 
 template <int KS>
-static hipError_t launch_decode_t(KParams p, int bg_req, hipStream_t st) {
-    p.n_rs = (p.out + kDecodeRows - 1) / kDecodeRows;
-    p.n_ks = p.in / KS;
+static hipError_t launch_decode_t(KGroup& grp, int bg_req, hipStream_t st) {
     // block groups: enough workgroups to fill the chip once (one per compute unit), few
     // enough that each walks through several blocks and amortises its prologue and tail
-    const int pairs = p.n_rs * p.n_ks;
-    int bg = bg_req;
-    if (bg <= 0) {
-        // largest group count that still fits on the chip in one round; among those prefer
-        // one that gives every workgroup the same number of blocks
-        bg = 256 / pairs;
-        if (bg < 1) bg = 1;
-        if (bg > p.n_loaded) bg = p.n_loaded;
-        for (int cand = bg; cand >= 1 && cand * 4 >= bg * 3; --cand)
-            if (p.n_loaded % cand == 0) {
-                bg = cand;
-                break;
-            }
+    int total_pairs = 0;
+    for (int i = 0; i < grp.count; ++i) {
+        KParams& p = grp.s[i];
+        p.n_rs = (p.out + kDecodeRows - 1) / kDecodeRows;
+        p.n_ks = p.in / KS;
+        total_pairs += p.n_rs * p.n_ks;
     }
-    if (bg > p.n_loaded) bg = p.n_loaded;
-    while ((p.n_loaded + bg - 1) / bg > kMaxBlocksPerWg) ++bg;
-    p.n_bg = bg;
-    if (p.n_rs > kCounterSlots || p.n_ks * bg > p.part_slots) return hipErrorInvalidValue;
+    unsigned next = 0;
+    for (int i = 0; i < grp.count; ++i) {
+        KParams& p = grp.s[i];
+        int bg = bg_req;
+        if (bg <= 0) {
+            // largest group count that still fits on the chip in one round; among those prefer
+            // one that gives every workgroup the same number of blocks
+            bg = 256 / total_pairs;
+            if (bg < 1) bg = 1;
+            if (bg > p.n_loaded) bg = p.n_loaded;
+            for (int cand = bg; cand >= 1 && cand * 4 >= bg * 3; --cand)
+                if (p.n_loaded % cand == 0) {
+                    bg = cand;
+                    break;
+                }
+        }
+        if (bg > p.n_loaded) bg = p.n_loaded;
+        while ((p.n_loaded + bg - 1) / bg > kMaxBlocksPerWg) ++bg;
+        p.n_bg = bg;
+        if (p.n_rs > kCounterSlots || p.n_ks * bg > p.part_slots) return hipErrorInvalidValue;
+        grp.base[i] = next;
+        next += (unsigned(p.n_rs * p.n_ks) * unsigned(bg) + 7u) & ~7u;
+    }
+    for (int i = grp.count; i <= kMaxGroup; ++i) grp.base[i] = next;
     const size_t smem = size_t(KS) * 68 + 2 * size_t(kDecodeRows) * 32 + size_t(kProducers) * kMaxBlocksPerWg * 4 +
                         96 * 4 + 16;
     static bool attr_set = false;
@@ -661,24 +712,33 @@ static hipError_t launch_decode_t(KParams p, int bg_req, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const unsigned grid = unsigned(pairs) * unsigned(bg);
-    hipLaunchKernelGGL((k_decode<KS>), dim3(grid), dim3((kConsumers + kProducers) * 64), smem, st, p);
+    hipLaunchKernelGGL((k_decode<KS>), dim3(next), dim3((kConsumers + kProducers) * 64), smem, st, grp);
     return hipGetLastError();
 }
 
-hipError_t launch_decode(const LaunchArgs& a, hipStream_t st) {
-    KParams p = make_params(a);
+hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st) {
+    if (count < 1 || count > kMaxGroup) return hipErrorInvalidValue;
     const DecodeTuning& tn = decode_tuning();
     int ks = tn.kslab;
-    if (ks == 0) ks = a.geo.min_slab;
-    if (ks < a.geo.min_slab || p.in % ks) return hipErrorInvalidValue;   // workspace is sized for min_slab
-    const size_t sign_span = size_t(a.geo.n) * a.geo.block_stride;
-    if (sign_span + 4096 >= (size_t(1) << 32)) return hipErrorInvalidValue;   // 32-bit buffer offsets
-    p.sign_bytes_total = unsigned(sign_span);
-    if (ks == 1024) return launch_decode_t<1024>(p, tn.bgroups, st);
-    if (ks == 512) return launch_decode_t<512>(p, tn.bgroups, st);
-    if (ks == 256) return launch_decode_t<256>(p, tn.bgroups, st);
+    if (ks == 0) ks = a[0].geo.min_slab;
+    KGroup grp;
+    grp.count = count;
+    for (int i = 0; i < count; ++i) {
+        if (a[i].batch != 1 || a[i].n_loaded < 1) return hipErrorInvalidValue;
+        // the workspace of an image is sized for its own min_slab; one kernel, one slab width
+        if (ks < a[i].geo.min_slab || a[i].geo.in % ks) return hipErrorInvalidValue;
+        const size_t sign_span = size_t(a[i].geo.n) * a[i].geo.block_stride;
+        if (sign_span + 4096 >= (size_t(1) << 32)) return hipErrorInvalidValue;   // 32-bit buffer offsets
+        grp.s[i] = make_params(a[i]);
+        grp.s[i].sign_bytes_total = unsigned(sign_span);
+    }
+    for (int i = count; i < kMaxGroup; ++i) grp.s[i] = grp.s[0];
+    if (ks == 1024) return launch_decode_t<1024>(grp, tn.bgroups, st);
+    if (ks == 512) return launch_decode_t<512>(grp, tn.bgroups, st);
+    if (ks == 256) return launch_decode_t<256>(grp, tn.bgroups, st);
     return hipErrorInvalidValue;
 }
+
+hipError_t launch_decode(const LaunchArgs& a, hipStream_t st) { return launch_decode_group(&a, 1, st); }
 
 }  // namespace bitstack

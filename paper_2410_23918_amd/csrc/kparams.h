@@ -25,6 +25,16 @@ struct KParams {
     int y_f32;
 };
 
+// Several decode calls that read the same activation vector, merged into one launch: workgroup
+// ids [base[i], base[i + 1]) belong to stack i (ranges padded to multiples of 8, so that the id
+// modulo 8 -- the XCD a workgroup lands on -- means the same for every stack).
+constexpr int kMaxGroup = 4;
+struct KGroup {
+    KParams s[kMaxGroup];
+    unsigned base[kMaxGroup + 1];
+    int count;
+};
+
 inline KParams make_params(const LaunchArgs& a) {
     KParams p;
     p.x = static_cast<const __half*>(a.x);

@@ -179,6 +179,18 @@ def test_cfg2_llama_attn_proj_true_iavd(B):
             err = O.relative_error(y, ref)
             print(f"cfg2 n_loaded={nl} kernel={kern}: rel err {err:.2e}", flush=True)
             assert err <= TOL
+    # few block groups: a workgroup walks through many blocks (more than the number whose slab
+    # maxima are prepared before the first barrier), many partial rows per row slab otherwise
+    ref = O.forward_dense(st, x, 16)
+    for bg in (1, 2, 3, 16):
+        B.set_option(B.OPT_DECODE_BGROUPS, bg)
+        try:
+            y = _run(B, ps, x, 16, B.KERNEL_DECODE)
+        finally:
+            B.set_option(B.OPT_DECODE_BGROUPS, 0)
+        err = O.relative_error(y, ref)
+        print(f"cfg2 n_loaded=16 block groups={bg}: rel err {err:.2e}", flush=True)
+        assert err <= TOL
     sw2, U2, V2 = ps.unpack_block(15)
     assert np.array_equal(sw2, st.sign_words()[15])
 
@@ -229,6 +241,49 @@ def test_cfg4_decoder_layer_variable_stack_heights(B):
         print(f"cfg4 {name} {out}x{inn} n_loaded={nl}: {err:.2e}", flush=True)
         assert err <= TOL
         del ps
+    synth_stack.cache_clear()
+
+
+def test_cfg4_layer_through_one_native_call_with_merged_launches(B):
+    """The seven linears of a decoder layer as one job list: q/k/v read one vector, gate/up
+    another, so the native loop merges them into grouped launches (3 + 1 + 2 + 1 jobs).  Every
+    output is checked against the oracle on sampled rows and against its own single launch; a
+    second pass over the same list checks that the workspaces were left clean."""
+    import torch
+    rng = W.rng_for(4, 0)
+    nl_all = W.variable_n_loaded(rng, 32 * 7)
+    shapes = W.llama3_8b_layer_shapes()
+    xs = {4096: _to_dev(acts(4, 1, 4096, tag=100)[0]), 14336: _to_dev(acts(4, 1, 14336, tag=101)[0])}
+    x_o = _to_dev(acts(4, 1, 4096, tag=102)[0])
+    items, keep = [], []
+    for m, (name, out, inn) in enumerate(shapes):
+        nl = int(nl_all[m])
+        st = synth_stack(4, out, inn, nl, tag=m)
+        ps = _pack(B, st)
+        x = x_o if name == "o_proj" else xs[inn]
+        y = torch.full((out,), float("nan"), dtype=torch.float16, device="cuda:0")
+        items.append((x, ps, nl, y))
+        keep.append((name, st, nl))
+    jobs = B.make_jobs(items)
+    rows_rng = W.rng_for(4, 2)
+    for rep in range(2):
+        for it in items:
+            it[3].fill_(float("nan"))
+        B.linear_many(jobs)
+        torch.cuda.synchronize()
+        for (name, st, nl), (x, ps, _, y) in zip(keep, items):
+            out = y.shape[0]
+            rows = np.sort(rows_rng.choice(out, size=128, replace=False))
+            xin = x.cpu().numpy()[None, :]
+            ref = O.forward_rows(st, xin, nl, rows)
+            got = y.float().cpu().numpy().astype(np.float64)[None, :]
+            assert np.isfinite(got).all()
+            err = O.relative_error(got[:, rows], ref)
+            single = ps.linear(x, nl).float().cpu().numpy().astype(np.float64)[None, :]
+            dev = O.relative_error(got, single)
+            print(f"cfg4 merged pass {rep} {name} n_loaded={nl}: vs oracle {err:.2e}, vs single launch {dev:.2e}", flush=True)
+            assert err <= TOL and dev <= 1e-3
+    del jobs, items
     synth_stack.cache_clear()
 
 
