@@ -430,9 +430,12 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
                 }
             }
         };
+        BS_TRACE2(1, 16);
         slab_max(0);
+        BS_TRACE2(1, 17);
         lds_barrier();   // P1
         BS_TRACE(1);
+        BS_TRACE2(1, 18);
         if (nb > NPRE) {   // same for the whole workgroup
             for (int qb = NPRE; qb < nb; qb += NPRE) {
 #pragma unroll
@@ -447,9 +450,13 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
         }
         BS_TRACE(2);
         Raw rb = load_raw(1);
+        BS_TRACE2(1, 19);
         quantise(0, ra);
+        BS_TRACE2(1, 20);
         store_u(0, u0);
+        BS_TRACE2(1, 21);
         lds_barrier();   // P3
+        BS_TRACE2(1, 22);
         BS_TRACE(3);
         // interval q: stage block q + 1 (raw V already here), fetch block q + 2's raw V
         for (int q = 0; q < nb; q += 2) {
@@ -524,7 +531,8 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
 #pragma unroll
                     for (int t = 0; t < 8; ++t) {
                         // next fragment is requested before this one is used (LDS latency
-                        // hidden behind the matrix-core instructions of this one)
+                        // hidden behind the matrix-core instructions of this one; requesting two
+                        // steps ahead measured no faster)
                         v4i Tn = Tf;
                         if (c * 8 + t + 1 < NCH * 8) Tn = frag[(c * 8 + t + 1) * 64 + lane];
                         const int mask = 0x01010101 << (t & 3);
@@ -573,8 +581,10 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
 
         lds_barrier();   // P1
         BS_TRACE(1);
-        // The sign stream starts only now: requested at kernel entry it would fill the memory
-        // queues ahead of the few loads the producers' prologue is waiting for.
+        // The sign stream starts only now.  Requested at kernel entry it would not arrive sooner:
+        // a wavefront cannot even issue its 16 KiB window faster than the memory system, asked by
+        // every compute unit at once, takes requests (the issue alone lasts ~2.4 us), so it would
+        // only reach this barrier later and hold up the producers' prologue.
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
 #pragma unroll
@@ -620,30 +630,34 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
     if (*flag) {
         // One pass with every load in flight at once: thread = (4 consecutive rows, a third of
         // the slots), 128-bit loads; the three partial sums meet in LDS.  Fixed summation order,
-        // so the result does not depend on which workgroup arrived last.  The acquire makes this
-        // compute unit's caches drop what they hold of the workspace (rows written during an
-        // earlier call may still sit in this XCD's L2); the loads after it are ordinary ones.
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        // so the result does not depend on which workgroup arrived last.  The loads carry agent
+        // scope themselves (they miss in every cache that is not coherent across XCDs, where rows
+        // written during an earlier call may still sit), so no cache invalidate is paid.
         static_assert(NT == 768 && RS == 1024, "finisher mapping: 256 row quads x 3 slot groups");
         const int nslots = p.n_ks * p.n_bg;
         const int rq = tid & 255, sg = tid >> 8;
         const int row = row0 + 4 * rq;
         const bool live = row < p.out;   // out is a multiple of 32: a quad is inside or outside as a whole
         float4 tot = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (live) {
-            const float* src = p.part + row;
-            constexpr int MAXK = 24;     // slots per group and round
+        {
+            // descriptor over this row slab's column of the workspace; slots past the end or rows
+            // past the matrix get an offset beyond it (reads as zero, no traffic)
+            const unsigned span = unsigned(size_t(nslots) * p.out * 4);
+            __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(p.part, 0, span, 0x00020000);
+            constexpr int kAgentScope = 16;   // sc1
+            constexpr int MAXK = 24;          // slots per group and round
             for (int base = 0; base < nslots; base += 3 * MAXK) {
-                float4 v[MAXK];
+                v4i v[MAXK];
 #pragma unroll
                 for (int k = 0; k < MAXK; ++k) {
                     const int sl = base + 3 * k + sg;
-                    v[k] = sl < nslots ? *reinterpret_cast<const float4*>(src + size_t(sl) * p.out)
-                                       : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    const unsigned off = (live && sl < nslots) ? unsigned((size_t(sl) * p.out + row) * 4) : span;
+                    v[k] = __builtin_amdgcn_raw_buffer_load_b128(prs, off, 0, kAgentScope);
                 }
 #pragma unroll
                 for (int k = 0; k < MAXK; ++k) {
-                    tot.x += v[k].x; tot.y += v[k].y; tot.z += v[k].z; tot.w += v[k].w;
+                    tot.x += __int_as_float(v[k][0]); tot.y += __int_as_float(v[k][1]);
+                    tot.z += __int_as_float(v[k][2]); tot.w += __int_as_float(v[k][3]);
                 }
             }
         }

@@ -99,3 +99,13 @@ def test_error_codes_on_the_host():
     assert L.bitstack_set_option(99, 1) == -8
     assert B.strerror(-5).startswith("scale")
     assert B.strerror(0) == "ok"
+
+
+def test_bench_sign_packing_matches_oracle():
+    """bench.py packs its synthetic sign matrices itself (it may touch the oracle only in its CPU
+    baseline leg); the words must be the canonical ones."""
+    import importlib
+    bench = importlib.import_module("bench")
+    from oracle import bitstack_oracle as O
+    b = bench.Blocks(96, 512, 3, 3)
+    assert np.array_equal(b.sign_words(), O.Stack(b.S, b.U, b.V, b.s).sign_words())
