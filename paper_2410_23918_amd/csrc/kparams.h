@@ -23,6 +23,7 @@ struct KParams {
     int out, in, batch, n_loaded;
     int n_rs, n_ks;       // row slabs, column slabs per block
     int y_f32;
+    __half* xpack;        // activation scratch in fragment order (null if the image has none)
 };
 
 // Several decode calls that read the same activation vector, merged into one launch: workgroup
@@ -55,6 +56,7 @@ inline KParams make_params(const LaunchArgs& a) {
     p.n_loaded = a.n_loaded;
     p.n_rs = p.n_ks = 0;
     p.y_f32 = a.y_f32 ? 1 : 0;
+    p.xpack = a.geo.xpack_bytes ? reinterpret_cast<__half*>(a.image + a.geo.off_xpack) : nullptr;
     return p;
 }
 

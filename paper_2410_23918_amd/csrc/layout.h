@@ -23,12 +23,14 @@
 // U rows.  Plain row-major [out][16].
 //
 // The image of a whole stack is
-//   [ 1/s : in floats ][ block 0 ] ... [ block n-1 ][ row maxima ][ partial sums ][ counters ]
+//   [ 1/s : in floats ][ block 0 ] ... [ block n-1 ][ row maxima ][ partial sums ][ counters ][ activation scratch ]
 // with every part 256-byte aligned.  "Row maxima" is derived data, not part of a
 // block: per block and input channel j, max_r |V[j][r]| as fp16 in panel order; it
 // lets the decode kernel find the exact max |V[j][r] * x[j]/s[j]| of a column slab
 // from one value per channel instead of sixteen.  The partial-sum workspace holds
-// one fp32 row of `out` values per workgroup that shares a row slab.
+// one fp32 row of `out` values per workgroup that shares a row slab.  Images packed
+// for more than 64 tokens per call end with a scratch area of max_batch x in fp16
+// values, where the prefill kernel keeps the activations in fragment order.
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
@@ -46,6 +48,7 @@ constexpr int kTileRows = 32;      // rows per sign unit
 constexpr int kChunkCols = 256;    // columns per sign unit
 constexpr int kUnitBytes = 1024;
 constexpr int kCounterSlots = 4096; // split-accumulation arrival counters
+constexpr int kSmallBatch = 64;     // batches up to this size need no activation scratch
 
 struct Geometry {
     int out, in, n, max_batch;
@@ -59,6 +62,8 @@ struct Geometry {
     int part_slots;      // n * (in / min_slab)
     int min_slab;        // smallest column slab the decode kernel may use with this image
     size_t off_ctr;      // uint32[kCounterSlots], zero between calls
+    size_t off_xpack;    // fp16 activations of a large batch in matrix-core fragment order (max_batch > 64 only)
+    size_t xpack_bytes;
     size_t total;
 };
 
@@ -82,7 +87,9 @@ BS_HD Geometry make_geometry(int out, int in, int n, int max_batch) {
     g.off_vmax = align256(g.off_blocks + size_t(n) * g.block_stride);
     g.off_part = align256(g.off_vmax + size_t(n) * size_t(in) * 2);
     g.off_ctr = align256(g.off_part + size_t(g.part_slots) * size_t(out) * 4);
-    g.total = align256(g.off_ctr + size_t(kCounterSlots) * 4);
+    g.off_xpack = align256(g.off_ctr + size_t(kCounterSlots) * 4);
+    g.xpack_bytes = max_batch > kSmallBatch ? size_t((max_batch + 31) / 32 * 32) * size_t(in) * 2 : 0;
+    g.total = align256(g.off_xpack + g.xpack_bytes);
     return g;
 }
 

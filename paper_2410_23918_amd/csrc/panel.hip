@@ -20,6 +20,7 @@
 //      weight tile on the matrix cores (fp32 accumulate).  The weight tile is built once per
 //      chunk for all token tiles of the workgroup.
 #include <hip/hip_fp16.h>
+#include <type_traits>
 #include <hip/hip_runtime.h>
 
 #include "kernels.h"
@@ -37,7 +38,7 @@ constexpr int kPanelLd = 264;         // fp16 elements per LDS row of a 256-colu
 // A V chunk (256 columns x 16 ranks) in LDS, kept in the order it has in memory: 16 panel positions
 // (t, g) x 16 ranks, one row of 16 columns (32 B) each.  Rows are spaced 48 B and positions 784 B so
 // that both the 128-bit row writes and the 16-bit gathers "one column, 8 ranks" spread over all banks.
-constexpr int kFusedMaxBatch = 64;    // above this the weight-tile kernel is used
+constexpr int kFusedMaxBatch = kSmallBatch;   // above this the weight-tile kernels are used
 constexpr int kVRow = 48;
 constexpr int kVPos = 16 * kVRow + 16;
 constexpr int kVBuf = 16 * kVPos;
@@ -528,10 +529,319 @@ static hipError_t launch_fused(const KParams& p, hipStream_t st) {
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Many tokens (prefill): the weight tile is kept, but built the way the small-batch kernel builds
+// its signed tiles.  Per block, the signed fp16 tile (same 1.5 vector instructions per element) is
+// multiplied by a permuted identity on the matrix cores, which adds it to an fp32 accumulator tile
+// in the same register layout; after the last block the tile is scaled by 1/s (Eq. 4 moved from the
+// activations to the weight columns, so that activation fragments come from memory untouched),
+// rounded to fp16 and parked in LDS.  Then every wavefront multiplies the two parked tiles (64 rows
+// x 2 x 256 columns) with its own 64 of the workgroup's 512 tokens.  Same teams, private LDS
+// pieces, U cache and three-deep input rotation as k_fused; two LDS-only barriers per pair of
+// column chunks.
+// Activations of a large batch, once per call, into the order the product stage reads them:
+// fragment (token group of 32, 16 columns) = 64 lanes x 8 values, lane (token ln, half hl) holding
+// columns 8*hl .. 8*hl + 7.  A wavefront then fetches a fragment as 1 KiB of consecutive memory
+// instead of 32-byte pieces of 32 token rows.  Tokens past the batch are zero.
+__global__ __launch_bounds__(256) void k_xpack(const __half* x, __half* xp, int batch, int in) {
+    const int frags_per_group = in / 16;
+    const size_t item = size_t(blockIdx.x) * 256 + threadIdx.x;          // one lane of one fragment
+    const size_t total = size_t((batch + 31) / 32) * frags_per_group * 64;
+    if (item >= total) return;
+    const int lane = int(item & 63);
+    const size_t frag = item >> 6;
+    const int ks = int(frag % frags_per_group), tgp = int(frag / frags_per_group);
+    const int tok = tgp * 32 + (lane & 31);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (tok < batch) v = *reinterpret_cast<const uint4*>(x + size_t(tok) * in + ks * 16 + 8 * (lane >> 5));
+    *reinterpret_cast<uint4*>(xp + item * 8) = v;
+}
+
+constexpr int kTileFixedLds = 8 * 2 * kVPriv + 2 * kPanelRows * kPanelLd * 2;
+constexpr int kTileMaxBlocks = (160 * 1024 - kTileFixedLds) / 2048 - 1;
+constexpr int kTileTokens = 512;   // tokens per workgroup
+
+__global__ __launch_bounds__(512) void k_tile(KParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int team = wave >> 2, cw = wave & 3;
+    const int hl = lane >> 5, ln = lane & 31;
+    unsigned char* const vpriv = smem + wave * (2 * kVPriv);
+    _Float16* const wt = reinterpret_cast<_Float16*>(smem + 8 * 2 * kVPriv);   // [team][64][kPanelLd]
+    unsigned char* const ucache = smem + kTileFixedLds;                         // [block][64 rows][32 B]
+    const int nch = p.in / kChunkCols;
+    const int iters = (nch + 1) / 2;
+    const int n = p.n_loaded;
+    const int total = iters * n;
+    const int rt0 = blockIdx.x * 2, nrt = p.out / kTileRows;
+    const int rtc[2] = {min(rt0, nrt - 1), min(rt0 + 1, nrt - 1)};   // clamped for loads
+    const int tok_w = blockIdx.y * kTileTokens + wave * 64;           // my first token in the product stage
+
+    for (int idx = tid; idx < n * 128; idx += 512) {   // U rows of my 64 output rows, all blocks -> LDS
+        const int i = idx >> 7, piece = idx & 127;
+        const int row = rtc[piece >> 6] * kTileRows + ((piece >> 1) & 31);
+        *reinterpret_cast<uint4*>(ucache + idx * 16) = *reinterpret_cast<const uint4*>(
+            p.blocks + size_t(i) * p.block_stride + p.off_u + size_t(row) * 32 + (piece & 1) * 16);
+    }
+
+    struct Pos {
+        int it, i;
+    };
+    auto advance = [&](Pos q) -> Pos {
+        if (++q.i == n) {
+            q.i = 0;
+            ++q.it;
+        }
+        return q;
+    };
+    auto chunk_of = [&](Pos q) -> int { return min(2 * q.it + team, nch - 1); };
+    auto block_of = [&](Pos q) -> const unsigned char* { return p.blocks + size_t(q.i) * p.block_stride; };
+    struct VIn {
+        uint4 a, b;
+    };
+    const unsigned voff = unsigned((((lane >> 3) * 2 + (cw >> 1)) * 16 + 2 * (lane & 7)) * 32 + (cw & 1) * 16);
+    auto fetch_v = [&](Pos q) -> VIn {
+        const unsigned char* src = block_of(q) + p.off_v + size_t(chunk_of(q)) * 8192;
+        VIn v;
+        v.a = *reinterpret_cast<const uint4*>(src + voff);
+        v.b = *reinterpret_cast<const uint4*>(src + voff + 32);
+        return v;
+    };
+    struct SIn {
+        uint2 w[2];
+    };
+    const unsigned soff[2] = {unsigned((size_t(rtc[0]) * nch) * kUnitBytes + ((cw >> 1) * 32 + ln) * 16 + (cw & 1) * 8),
+                              unsigned((size_t(rtc[1]) * nch) * kUnitBytes + ((cw >> 1) * 32 + ln) * 16 + (cw & 1) * 8)};
+    auto fetch_s = [&](Pos q) -> SIn {
+        const unsigned char* src = block_of(q) + size_t(chunk_of(q)) * kUnitBytes;
+        SIn v;
+        v.w[0] = *reinterpret_cast<const uint2*>(src + soff[0]);
+        v.w[1] = *reinterpret_cast<const uint2*>(src + soff[1]);
+        return v;
+    };
+    unsigned char* const vdst = vpriv + ((lane >> 3) * kVtStride + 2 * (lane & 7) * 4) * 4;
+    int vsrc_off[2];
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile) {
+        const int b = ln >> 3, t = ln & 7, e = tile * 4 + b;
+        vsrc_off[tile] = (t * kVtStride + 8 * hl * 4) * 4 + e * 2;
+    }
+    auto stage_v = [&](VIn v, int buf) {
+        *reinterpret_cast<uint4*>(vdst + buf * kVPriv) = v.a;
+        *reinterpret_cast<uint4*>(vdst + buf * kVPriv + 16) = v.b;
+    };
+    auto read_vf = [&](int buf, int tile) -> v8h {
+        v8h vf;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            vf[k] = *reinterpret_cast<const _Float16*>(vpriv + buf * kVPriv + vsrc_off[tile] + k * 16);
+        return vf;
+    };
+    auto read_u = [&](int i, int rg) -> v8h {
+        return *reinterpret_cast<const v8h*>(ucache + ((i * 64 + rg * 32 + ln) * 2 + hl) * 16);
+    };
+
+    // permuted identities: A[i'][slot s of half hl] = 1 where i' is the column that slot s of the
+    // signed tile holds (8*mf + 4*hl + s/2 + 16*(s%2)), so that identity x tile = tile in the
+    // accumulator layout "register v <-> column 8*(v/4) + 4*hl + v%4"
+    v8h ident[2];
+#pragma unroll
+    for (int mf = 0; mf < 2; ++mf)
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl)
+            ident[mf][sl] = _Float16(ln == 8 * mf + 4 * hl + (sl >> 1) + 16 * (sl & 1) ? 1.0f : 0.0f);
+
+    v16f wacc[2][2];   // [tile][row group]: the weight tile of this chunk, fp32 (starts at a chunk's first block)
+    v16f yacc[2][2];   // [row group][token group of my 64 tokens]
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) yacc[a][b][v] = 0.0f;
+
+    // first = the chunk's first block: the accumulator starts from zero instead of being cleared
+    // beforehand, so that its 64 registers are free during the product stage
+    auto rebuild = [&](auto first, const SIn& sg, v8h uf0, v8h uf1, v8h vf0, v8h vf1) {
+#pragma unroll
+        for (int tile = 0; tile < 2; ++tile) {
+            const v8h vf = tile ? vf1 : vf0;
+#pragma unroll
+            for (int rg = 0; rg < 2; ++rg) {
+                v16f z;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                const v16f m = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, rg ? uf1 : uf0, z, 0, 0, 0);
+                const unsigned wrd = ~(tile ? sg.w[rg].y : sg.w[rg].x) >> (4 * hl);
+#pragma unroll
+                for (int mf = 0; mf < 2; ++mf) {
+                    unsigned r4[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+                        h2 c;
+                        c[0] = _Float16(m[4 * mf + k]);
+                        c[1] = _Float16(m[4 * mf + k + 8]);
+                        const unsigned flip = (wrd << (15 - 8 * mf - k)) & 0x80008000u;
+                        r4[k] = __builtin_bit_cast(unsigned, c) ^ flip;
+                    }
+                    if (decltype(first)::value && mf == 0)
+                        wacc[tile][rg] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ident[mf], __builtin_bit_cast(v8h, r4), z, 0, 0, 0);
+                    else
+                        wacc[tile][rg] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ident[mf], __builtin_bit_cast(v8h, r4),
+                                                                                wacc[tile][rg], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    // end of a chunk: park my piece of W' diag(1/s) in LDS, then the product stage for both teams' chunks
+    auto flush_and_multiply = [&](int it) {
+        const int ch = min(2 * it + team, nch - 1);
+#pragma unroll
+        for (int tile = 0; tile < 2; ++tile)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int c = cw * 64 + tile * 32 + 8 * q4 + 4 * hl;   // first of 4 consecutive columns
+                const float4 r = *reinterpret_cast<const float4*>(p.rs + ch * kChunkCols + c);
+#pragma unroll
+                for (int rg = 0; rg < 2; ++rg) {
+                    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                    h4 o;
+                    o[0] = _Float16(wacc[tile][rg][4 * q4 + 0] * r.x);
+                    o[1] = _Float16(wacc[tile][rg][4 * q4 + 1] * r.y);
+                    o[2] = _Float16(wacc[tile][rg][4 * q4 + 2] * r.z);
+                    o[3] = _Float16(wacc[tile][rg][4 * q4 + 3] * r.w);
+                    *reinterpret_cast<h4*>(wt + (team * kPanelRows + rg * 32 + ln) * kPanelLd + c) = o;
+                }
+            }
+        lds_barrier();   // both tiles parked
+        if (tok_w < p.batch) {
+            // fragments of my two token groups: [group][in / 16][64 lanes][8]
+            const __half* xrow[2];
+#pragma unroll
+            for (int tg = 0; tg < 2; ++tg)
+                xrow[tg] = p.xpack + (size_t(min(tok_w / 32 + tg, (p.batch - 1) / 32)) * (p.in / 16) * 64 + lane) * 8;
+            // activation fragments are requested PD steps ahead of their use (they come from L2 or
+            // beyond), weight fragments one step ahead (LDS); a step = 16 columns of one of the two tiles
+            constexpr int PD = 8;
+            const int nks = (2 * it + 1 < nch) ? 32 : 16;   // odd chunk count: the second team's last tile is not a chunk
+            const __half* const x0 = xrow[0] + size_t(2 * it) * 16 * 512;
+            const __half* const x1 = xrow[1] + size_t(2 * it) * 16 * 512;
+            auto wfrag = [&](int ks, int rg) -> v8h {
+                return *reinterpret_cast<const v8h*>(wt + ((ks >> 4) * kPanelRows + rg * 32 + ln) * kPanelLd + (ks & 15) * 16 + 8 * hl);
+            };
+            v8h ring[PD][2];
+#pragma unroll
+            for (int k = 0; k < PD; ++k) {
+                ring[k][0] = *reinterpret_cast<const v8h*>(x0 + size_t(k) * 512);
+                ring[k][1] = *reinterpret_cast<const v8h*>(x1 + size_t(k) * 512);
+            }
+            v8h b0 = wfrag(0, 0), b1 = wfrag(0, 1);
+            for (int kb = 0; kb < nks; kb += PD) {   // nks is a multiple of PD
+#pragma unroll
+                for (int k = 0; k < PD; ++k) {
+                    const int ks = kb + k;
+                    const v8h a0 = ring[k][0], a1 = ring[k][1];
+                    const int kn = min(ks + PD, nks - 1);
+                    ring[k][0] = *reinterpret_cast<const v8h*>(x0 + size_t(kn) * 512);
+                    ring[k][1] = *reinterpret_cast<const v8h*>(x1 + size_t(kn) * 512);
+                    const int k1 = min(ks + 1, nks - 1);
+                    const v8h nb0 = wfrag(k1, 0), nb1 = wfrag(k1, 1);
+                    yacc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, b0, yacc[0][0], 0, 0, 0);
+                    yacc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b0, yacc[0][1], 0, 0, 0);
+                    yacc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, b1, yacc[1][0], 0, 0, 0);
+                    yacc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b1, yacc[1][1], 0, 0, 0);
+                    b0 = nb0;
+                    b1 = nb1;
+                }
+            }
+        }
+        lds_barrier();   // tiles free for the next pair of chunks
+    };
+
+    Pos q = {0, 0};
+    VIn vA = fetch_v(q);
+    SIn sA = fetch_s(q);
+    q = advance(q);
+    VIn vB = fetch_v(q);
+    SIn sB = fetch_s(q);
+    q = advance(q);
+    Pos qv = advance(q);
+    VIn vC = fetch_v(q);
+    SIn sC;
+    stage_v(vA, 0);
+    v8h vf0 = read_vf(0, 0), vf1 = read_vf(0, 1);
+    __syncthreads();   // U cache complete
+
+    int ci = 0, it = 0;
+#define BS_TILE_STEP(S, CUR, NXT, FAR)                                                     \
+    {                                                                                      \
+        const v8h uf0 = read_u(ci, 0), uf1 = read_u(ci, 1);                                \
+        stage_v(v##NXT, ((S) + 1) & 1);                                                    \
+        const v8h vn0 = read_vf(((S) + 1) & 1, 0), vn1 = read_vf(((S) + 1) & 1, 1);        \
+        s##FAR = fetch_s(q);                                                               \
+        v##CUR = fetch_v(qv);                                                              \
+        q = advance(q);                                                                    \
+        qv = advance(qv);                                                                  \
+        if (ci == 0)                                                                       \
+            rebuild(std::true_type{}, s##CUR, uf0, uf1, vf0, vf1);                         \
+        else                                                                               \
+            rebuild(std::false_type{}, s##CUR, uf0, uf1, vf0, vf1);                        \
+        vf0 = vn0;                                                                         \
+        vf1 = vn1;                                                                         \
+        if (++ci == n) {                                                                   \
+            ci = 0;                                                                        \
+            if (it < iters) flush_and_multiply(it);                                        \
+            ++it;                                                                          \
+        }                                                                                  \
+    }
+    // steps past the last one (count rounded up to a multiple of three) only touch wacc
+    for (int s = 0; s < total; s += 3) {
+        BS_TILE_STEP(s, A, B, C)
+        BS_TILE_STEP(s + 1, B, C, A)
+        BS_TILE_STEP(s + 2, C, A, B)
+    }
+#undef BS_TILE_STEP
+
+    // C[i = token][n = row]: lane (row ln), register v holds token 8*(v/4) + 4*hl + v%4 of the group
+#pragma unroll
+    for (int rg = 0; rg < 2; ++rg)
+#pragma unroll
+        for (int tg = 0; tg < 2; ++tg)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int tok = tok_w + tg * 32 + 8 * (v >> 2) + 4 * hl + (v & 3);
+                const int row = (rt0 + rg) * kTileRows + ln;
+                if (tok < p.batch && row < p.out) store_y(p, size_t(tok) * p.out + row, yacc[rg][tg][v]);
+            }
+}
+
+static bool tile_fits(const KParams& p) { return p.n_loaded <= kTileMaxBlocks && p.xpack != nullptr; }
+
+static hipError_t launch_tile(const KParams& p, hipStream_t st) {
+    const size_t smem = size_t(kTileFixedLds) + size_t(p.n_loaded) * 2048;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tile),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           kTileFixedLds + kTileMaxBlocks * 2048);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const size_t lanes = size_t((p.batch + 31) / 32) * (p.in / 16) * 64;
+    hipLaunchKernelGGL(k_xpack, dim3(unsigned((lanes + 255) / 256)), dim3(256), 0, st, p.x, p.xpack, p.batch, p.in);
+    dim3 grid((p.out + 2 * kTileRows - 1) / (2 * kTileRows), (p.batch + kTileTokens - 1) / kTileTokens);
+    hipLaunchKernelGGL(k_tile, grid, dim3(512), smem, st, p);
+    return hipGetLastError();
+}
+
 hipError_t launch_panel(const LaunchArgs& a, hipStream_t st) {
     KParams p = make_params(a);
     if (a.n_loaded < 1 || a.batch < 1) return hipErrorInvalidValue;
     if (a.batch <= kFusedMaxBatch && fused_fits(p)) return launch_fused(p, st);
+    if (a.batch > kFusedMaxBatch && tile_fits(p)) return launch_tile(p, st);
     if (a.batch > 256) return launch_panel_t<4>(p, st);
     if (a.batch > 128) return launch_panel_t<2>(p, st);
     return launch_panel_t<1>(p, st);

@@ -149,6 +149,21 @@ def test_batch_kernels_every_tile_variant(B, out, inn, n):
             assert err <= TOL
 
 
+def test_batch_kernels_tall_stacks_fall_back(B):
+    """Stacks taller than the LDS cache of U rows in the two main batch kernels allows (44 and
+    29 blocks) are served by the weight-tile kernel that reads U from memory."""
+    out, inn, n = 64, 512, 46
+    st = synth_stack(3, out, inn, n)
+    ps = _pack(B, st, max_batch=200)
+    x = acts(3, 200, inn)
+    for b, nl in ((2, 46), (2, 44), (70, 46), (70, 30), (70, 29), (200, 31)):
+        want = O.forward_dense(st, x[:b], nl)
+        y = _run(B, ps, x[:b], nl, B.KERNEL_PANEL)
+        err = O.relative_error(y, want)
+        print(f"{out}x{inn} batch kernel B={b} n_loaded={nl}: {err:.2e}", flush=True)
+        assert err <= TOL
+
+
 def test_argument_errors_on_device(B):
     import torch
     st = synth_stack(3, 32, 256, 1)
