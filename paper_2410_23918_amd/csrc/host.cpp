@@ -218,21 +218,22 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w,
     } else {
         if (kernel == BITSTACK_KERNEL_AUTO) {
             // Per-token decode launches stream the blocks once per token.  The batch path has two
-            // kernels: up to 64 tokens, signed tiles are rebuilt per group of 32 tokens at ~1 us
-            // per block and pair of 256-column chunks of a 64-row tile; beyond that a weight tile
-            // is rebuilt once per 512 tokens at ~1.1 us per block and chunk.  Rates measured on
-            // MI355X; decode: ~2.4 GB/ms of block stream plus ~15 us per launch.
+            // kernels: up to 64 tokens, signed tiles are rebuilt per group of 32 tokens; beyond
+            // that a weight tile is rebuilt once per 512 tokens and multiplied with them.  Both
+            // take ~1 us per block and pair of 256-column chunks of a 64-row tile, the second
+            // another ~13 us per chunk pair for the product.  Rates measured on MI355X; decode:
+            // ~2.4 GB/ms of block stream plus ~15 us per launch.
             const double blk_bytes = double(g.block_stride);
             const double t_decode = batch * (15.0 + n_loaded * blk_bytes / 2.4e6);
             const int row_tiles = (g.out + 63) / 64;
-            const int chunks = g.in / 256;
+            const int chunk_pairs = (g.in / 256 + 1) / 2;
             double t_panel;
             if (batch <= 64) {
                 const int wgs = row_tiles * ((batch + 31) / 32);
-                t_panel = ((wgs + 255) / 256) * (15.0 + 1.0 * n_loaded * ((chunks + 1) / 2));
+                t_panel = ((wgs + 255) / 256) * (15.0 + 1.0 * n_loaded * chunk_pairs);
             } else {
                 const int wgs = row_tiles * ((batch + 511) / 512);
-                t_panel = ((wgs + 255) / 256) * (1.1 * n_loaded * chunks + 0.6 * chunks * ((batch < 512 ? batch : 512) / 128.0));
+                t_panel = ((wgs + 255) / 256) * (15.0 + chunk_pairs * (1.0 * n_loaded + 13.0));
             }
             kernel = (batch == 1 || t_decode <= t_panel) ? BITSTACK_KERNEL_DECODE : BITSTACK_KERNEL_PANEL;
         }
