@@ -147,7 +147,7 @@ def batch_table(B, torch, dev, n):
             torch.cuda.synchronize()
             us = e0.elapsed_time(e1) * 1e3 / reps
             tf = 2.0 * o * i * b / us / 1e6
-            kern = "k_fused" if b <= 64 else "k_panel"
+            kern = "k_fused" if b <= 64 else "k_xpack + k_tile"
             log(f"[bench] batch path {o}x{i} n={n} tokens={b} ({kern}): {us:.1f} us, {tf:.1f} useful TFLOP/s")
             rows.append({"shape": f"{o}x{i}", "tokens": b, "kernel": kern, "us": round(us, 1),
                          "useful_TFLOPs": round(tf, 2)})
