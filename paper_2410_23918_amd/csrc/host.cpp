@@ -229,8 +229,9 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w,
             const int chunk_pairs = (g.in / 256 + 1) / 2;
             double t_panel;
             if (batch <= 64) {
-                const int wgs = row_tiles * ((batch + 31) / 32);
-                t_panel = ((wgs + 255) / 256) * (15.0 + 1.0 * n_loaded * chunk_pairs);
+                const int split = small_batch_split(g.out, g.in, batch, g.part_slots);
+                const int wgs = row_tiles * ((batch + 31) / 32) * split;
+                t_panel = ((wgs + 255) / 256) * (15.0 + 1.0 * n_loaded * ((chunk_pairs + split - 1) / split)) + (split > 1 ? 5.0 : 0.0);
             } else {
                 const int wgs = row_tiles * ((batch + 511) / 512);
                 t_panel = ((wgs + 255) / 256) * (15.0 + chunk_pairs * (1.0 * n_loaded + 13.0));

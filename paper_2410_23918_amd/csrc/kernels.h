@@ -30,5 +30,7 @@ hipError_t launch_decode(const LaunchArgs& a, hipStream_t st);
 // up to 4 batch-1 calls in one launch; all must use the same column slab (Geometry::min_slab)
 hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st);
 hipError_t launch_panel(const LaunchArgs& a, hipStream_t st);
+// column split the small-batch kernel uses for this shape (1 = none)
+int small_batch_split(int out, int in, int batch, int part_slots);
 
 }  // namespace bitstack

@@ -272,8 +272,12 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
     unsigned char* const vpriv = smem + wave * (2 * kVPriv + kXPriv);
     _Float16* const xpriv = reinterpret_cast<_Float16*>(vpriv + 2 * kVPriv);
     unsigned char* const ucache = smem + kFusedFixedLds;   // [block][64 rows][32 B]
-    const int nch = p.in / kChunkCols;
-    const int iters = (nch + 1) / 2;
+    // column chunks of this workgroup: all of them, or one of ksplit ranges (blockIdx.z) when there are
+    // too few row tiles to fill the chip; the partial results then meet in the workspace (see the end)
+    const int ksplit = max(p.n_ks, 1);
+    const int nch_all = p.in / kChunkCols;
+    const int c_lo = int(blockIdx.z) * nch_all / ksplit, nch = (int(blockIdx.z) + 1) * nch_all / ksplit;   // [c_lo, nch)
+    const int iters = (nch - c_lo + 1) / 2;
     const int n = p.n_loaded;
     const int total = iters * n;
     const int rt0 = blockIdx.x * 2, nrt = p.out / kTileRows;
@@ -296,7 +300,7 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
     const int cg = lane & 7, tl = lane >> 3;   // staging role: 8 columns, tokens tl, tl + 8, ...
     auto fetch_x = [&](int it) -> XIn {         // chunk of my team's iteration `it`, clamped
         XIn v;
-        const int col = min(2 * it + team, nch - 1) * kChunkCols + cw * 64 + cg * 8;
+        const int col = min(c_lo + 2 * it + team, nch - 1) * kChunkCols + cw * 64 + cg * 8;
 #pragma unroll
         for (int m = 0; m < XPT; ++m)
             v.x[m] = *reinterpret_cast<const uint4*>(p.x + size_t(min(tok0 + tl + 8 * m, p.batch - 1)) * p.in + col);
@@ -306,7 +310,7 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
     };
     auto store_x = [&](XIn v, int it) {         // a team without a chunk left (odd chunk count) gets zeros
         const float rr[8] = {v.r0.x, v.r0.y, v.r0.z, v.r0.w, v.r1.x, v.r1.y, v.r1.z, v.r1.w};
-        const bool valid = 2 * it + team < nch;
+        const bool valid = c_lo + 2 * it + team < nch;
 #pragma unroll
         for (int m = 0; m < XPT; ++m) {
             const int tok = tl + 8 * m;
@@ -347,7 +351,7 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
         return q;
     };
     // past the last step the last chunk is read again, harmlessly
-    auto chunk_of = [&](Pos q) -> int { return min(2 * q.it + team, nch - 1); };
+    auto chunk_of = [&](Pos q) -> int { return min(c_lo + 2 * q.it + team, nch - 1); };
     auto block_of = [&](Pos q) -> const unsigned char* { return p.blocks + size_t(q.i) * p.block_stride; };
     // V: my wavefront needs, of every row (t, g, r) with g = my column half, the 8 columns
     // e = 8*(cw&1) .. +7, i.e. 16 of its 32 bytes; lane L takes rows (t = L/8, r = 2*(L%8) and + 1)
@@ -365,8 +369,8 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
     struct SIn {
         uint2 w[2];   // per row group: my row's two sign words of my 64 columns
     };
-    const unsigned soff[2] = {unsigned((size_t(rtc[0]) * nch) * kUnitBytes + ((cw >> 1) * 32 + ln) * 16 + (cw & 1) * 8),
-                              unsigned((size_t(rtc[1]) * nch) * kUnitBytes + ((cw >> 1) * 32 + ln) * 16 + (cw & 1) * 8)};
+    const unsigned soff[2] = {unsigned((size_t(rtc[0]) * nch_all) * kUnitBytes + ((cw >> 1) * 32 + ln) * 16 + (cw & 1) * 8),
+                              unsigned((size_t(rtc[1]) * nch_all) * kUnitBytes + ((cw >> 1) * 32 + ln) * 16 + (cw & 1) * 8)};
     auto fetch_s = [&](Pos q) -> SIn {
         const unsigned char* src = block_of(q) + size_t(chunk_of(q)) * kUnitBytes;
         SIn v;
@@ -494,6 +498,7 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
     // ---- the eight partial tiles meet in LDS; C[i = token][n = row]: lane (row ln),
     //      register v holds token 8*(v/4) + 4*hl + v%4 of the group
     float* red = reinterpret_cast<float*>(smem);   // [8][16][64]
+    float* const mine = p.part + size_t(blockIdx.z) * p.batch * p.out;   // my rows of the workspace (ksplit > 1)
 #pragma unroll
     for (int rg = 0; rg < 2; ++rg) {
         __syncthreads();
@@ -507,14 +512,70 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
             for (int w = 0; w < 8; ++w) sum += red[(w * 16 + v) * 64 + l];
             const int tok = tok0 + 8 * (v >> 2) + 4 * (l >> 5) + (v & 3);
             const int row = (rt0 + rg) * kTileRows + (l & 31);
-            if (tok < p.batch && row < p.out) store_y(p, size_t(tok) * p.out + row, sum);
+            if (tok < p.batch && row < p.out) {
+                if (ksplit == 1)
+                    store_y(p, size_t(tok) * p.out + row, sum);
+                else   // write-through: the reader may sit on another XCD
+                    __hip_atomic_store(mine + size_t(tok) * p.out + row, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
+    }
+    if (ksplit == 1) return;
+
+    // ---- column split: the last workgroup of this (row tile, token group) adds the ksplit partial
+    //      tiles in a fixed order and stores y (same protocol as the decode kernel: write-through
+    //      stores, one relaxed agent-scope counter after a barrier, agent-scope loads by the last one)
+    unsigned* const flag = reinterpret_cast<unsigned*>(smem + 32768);
+    __syncthreads();
+    unsigned* const ctr = p.ctr + blockIdx.y * gridDim.x + blockIdx.x;
+    if (tid == 0) {
+        const unsigned old = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *flag = (old + 1u == unsigned(ksplit)) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (*flag) {
+        // thread = (token of the group, 4 consecutive rows of the 64)
+        const int tok = tok0 + (tid >> 4), row = rt0 * kTileRows + 4 * (tid & 15);
+        if (tok < p.batch && row < p.out) {   // out is a multiple of 32: a quad is inside or outside as a whole
+            const unsigned span = unsigned(size_t(ksplit) * p.batch * p.out * 4);
+            __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(p.part, 0, span, 0x00020000);
+            constexpr int kAgentScope = 16;   // sc1
+            typedef int v4i_ __attribute__((ext_vector_type(4)));
+            v4i_ v[8];
+#pragma unroll
+            for (int z = 0; z < 8; ++z)
+                v[z] = __builtin_amdgcn_raw_buffer_load_b128(
+                    prs, z < ksplit ? unsigned(((size_t(z) * p.batch + tok) * p.out + row) * 4) : span, 0, kAgentScope);
+            float o4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int z = 0; z < 8; ++z)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) o4[k] += __int_as_float(v[z][k]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) store_y(p, size_t(tok) * p.out + row + k, o4[k]);
+        }
+        if (tid == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
 static bool fused_fits(const KParams& p) { return p.n_loaded <= kFusedMaxBlocks; }
 
-static hipError_t launch_fused(const KParams& p, hipStream_t st) {
+constexpr int kFusedMaxSplit = 8;
+
+// few row tiles: split the columns over several workgroups per tile (at least two chunks each;
+// the workspace must hold a partial row per split and token, the counters one slot per tile)
+int small_batch_split(int out, int in, int batch, int part_slots) {
+    const int wgs = ((out + 2 * kTileRows - 1) / (2 * kTileRows)) * ((batch + 31) / 32);
+    if (wgs >= 192 || wgs > kCounterSlots) return 1;
+    int ksplit = 256 / wgs;
+    ksplit = ksplit < kFusedMaxSplit ? ksplit : kFusedMaxSplit;
+    const int by_chunks = (in / kChunkCols) / 2, by_space = part_slots / batch;
+    ksplit = ksplit < by_chunks ? ksplit : by_chunks;
+    ksplit = ksplit < by_space ? ksplit : by_space;
+    return ksplit > 1 ? ksplit : 1;
+}
+
+static hipError_t launch_fused(KParams p, hipStream_t st) {
     const size_t smem = size_t(kFusedFixedLds) + size_t(p.n_loaded) * 2048;
     static bool attr_set = false;
     if (!attr_set) {
@@ -525,6 +586,8 @@ static hipError_t launch_fused(const KParams& p, hipStream_t st) {
         attr_set = true;
     }
     dim3 grid((p.out + 2 * kTileRows - 1) / (2 * kTileRows), (p.batch + 31) / 32);
+    p.n_ks = small_batch_split(p.out, p.in, p.batch, p.part_slots);
+    grid.z = p.n_ks;
     hipLaunchKernelGGL(k_fused, grid, dim3(512), smem, st, p);
     return hipGetLastError();
 }

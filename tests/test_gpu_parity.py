@@ -164,6 +164,31 @@ def test_batch_kernels_tall_stacks_fall_back(B):
         assert err <= TOL
 
 
+def test_small_batch_column_split_repeatable(B):
+    """Few row tiles: the small-batch kernel splits the columns over several workgroups whose
+    partial tiles meet in the workspace.  Results must not depend on arrival order (bit-identical
+    repeats), the counters must be left at zero (a decode call and another batch call follow), and
+    an odd split of the chunks (7 chunks over 3 ranges) must cover every column once."""
+    for out, inn, n, b in ((64, 4096, 6, 5), (160, 1792, 8, 2), (4096, 4096, 4, 16)):
+        st = synth_stack(3, out, inn, n)
+        ps = _pack(B, st, max_batch=b)
+        x = acts(3, b, inn)
+        ref = O.forward_dense(st, x, n)
+        first = None
+        for rep in range(3):
+            y = _run(B, ps, x, n, B.KERNEL_PANEL, "f32")
+            err = O.relative_error(y, ref)
+            assert err <= TOL, (out, inn, b, err)
+            if first is None:
+                first = y
+            else:
+                assert np.array_equal(first, y)
+            y1 = _run(B, ps, x[:1], n, B.KERNEL_DECODE)
+            assert O.relative_error(y1, ref[:1]) <= TOL
+        print(f"{out}x{inn} n={n} B={b} column split: {err:.2e}", flush=True)
+        del ps
+
+
 def test_argument_errors_on_device(B):
     import torch
     st = synth_stack(3, 32, 256, 1)
