@@ -197,9 +197,38 @@ def decoder_token(B, torch, dev, layers=32, n_pack=24):
     gbs = total_bytes / ms / 1e6
     log(f"[bench] decoder token: {len(items)} linears, {total_bytes / 1e9:.2f} GB of blocks, {ms:.3f} ms/token, "
         f"{gbs:.0f} GB/s ({gbs / HBM_PEAK_GBS * 100:.1f}% of 8 TB/s)")
+    # the same token as one captured graph (the launches carry no memset nodes); replayed with
+    # eager work between replays and compared with the eager outputs
+    ms_graph = None
+    try:
+        eager = [it[3].clone() for it in items[:14]]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            B.linear_many(jobs, 1, stream=side)
+        torch.cuda.current_stream().wait_stream(side)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            B.linear_many(jobs, 1, stream=torch.cuda.current_stream())
+        for _ in range(3):
+            for it in items[:14]:
+                it[3].zero_()
+            g.replay()
+            torch.cuda.synchronize()
+            assert all(torch.equal(a, it[3]) for a, it in zip(eager, items[:14])), "graph replay differs from eager"
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_graph = e0.elapsed_time(e1) / reps
+        log(f"[bench] decoder token as one graph: {ms_graph:.3f} ms/token, {total_bytes / ms_graph / 1e6:.0f} GB/s")
+    except Exception as ex:  # graphs are a side measurement
+        log(f"[bench] decoder token graph variant skipped: {type(ex).__name__}: {ex}")
     return {"linears": len(items), "block_stream_bytes": total_bytes, "ms_per_token": round(ms, 4),
             "GBps": round(gbs, 1), "pct_of_hbm_peak": round(gbs / HBM_PEAK_GBS * 100, 2),
-            "n_loaded": "U{8..24} per matrix, seeded", "launches_per_layer": 4}
+            "n_loaded": "U{8..24} per matrix, seeded", "launches_per_layer": 4,
+            "ms_per_token_graph": None if ms_graph is None else round(ms_graph, 4)}
 
 
 def main():

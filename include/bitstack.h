@@ -67,7 +67,8 @@ enum {
     BITSTACK_KERNEL_AUTO      = 0,
     BITSTACK_KERNEL_REFERENCE = 1, /* plain vector-ALU kernel, any batch <= max_batch            */
     BITSTACK_KERNEL_DECODE    = 2, /* matrix-core sign-stream kernel, one launch per token       */
-    BITSTACK_KERNEL_PANEL     = 3  /* weight tile rebuilt in LDS + matrix-core GEMM, any batch   */
+    BITSTACK_KERNEL_PANEL     = 3  /* batch kernels: weight rebuilt on chip (Eq. 8) and multiplied
+                                      with the activations on the matrix cores, any batch        */
 };
 
 /* Bytes of one residual block: (out*in + 16*k*(out+in)) / 8, Eq. (9) of the
@@ -76,8 +77,11 @@ enum {
 size_t bitstack_block_bytes(int out, int in, int k);
 
 /* Device bytes bitstack_pack_blocks needs for a stack of n blocks: 1/s, the n
- * blocks (each contiguous and self-contained, exactly bitstack_block_bytes long)
- * and an accumulation workspace for max_batch tokens.  0 for unsupported shapes. */
+ * blocks (each contiguous and self-contained, exactly bitstack_block_bytes long),
+ * per-channel maxima of V (in*2 bytes per block), an accumulation workspace
+ * (n * in/1024 rows of out floats) and, for max_batch > 64, a scratch area of
+ * max_batch (rounded up to 32) * in fp16 values in which a large batch of
+ * activations is rearranged once per call.  0 for unsupported shapes. */
 size_t bitstack_packed_bytes(int out, int in, int k, int n, int max_batch);
 
 /* Host only.  Canonical packing of the sign matrix of a float residual:
