@@ -125,10 +125,45 @@ int bitstack_unpack_blocks(const bitstack_weight_t* w, int block,
                            uint32_t* sign_words, uint16_t* U, uint16_t* V,
                            bitstack_stream_t stream);
 
+/* ---- Dynamic loading (Section 2.2: the model is a set of stacks of residual blocks that are
+ * loaded into and offloaded from memory one block at a time, in stack order, as the available
+ * memory changes; the appendix on minimal transmission units: a block is the unit that moves). */
+
+/* Host bytes of one block in device form plus its derived per-channel maxima, as
+ * bitstack_stage_block_host writes and bitstack_push_block reads them. */
+size_t bitstack_block_staging_bytes(int out, int in, int k);
+
+/* Host only.  Re-tiles one block (canonical sign words [out][in/32], U [out][k], V [in][k]) into
+ * its device form in `staging` (host memory of the caller, ideally pinned, at least
+ * bitstack_block_staging_bytes long). */
+int bitstack_stage_block_host(int out, int in, int k, const uint32_t* sign_words, const uint16_t* U,
+                              const uint16_t* V, void* staging, size_t staging_bytes);
+
+/* A stack with room for n_slots blocks and none loaded: stores 1/s and clears the workspace
+ * in caller-owned device memory of bitstack_packed_bytes(out,in,k,n_slots,max_batch) bytes.
+ * Synchronises the stream before returning. */
+int bitstack_create_stack(int out, int in, int k, int n_slots, int max_batch, const float* s,
+                          void* device_buf, size_t device_buf_bytes, bitstack_stream_t stream,
+                          bitstack_weight_t** handle);
+
+/* Loads the next block of the stack (index = bitstack_resident_blocks) from a staged host copy:
+ * two asynchronous host-to-device copies of exactly bitstack_block_bytes + in*2 bytes enqueued on
+ * `stream`; calls enqueued on that stream afterwards may use the block.  `staging` must stay
+ * unchanged until the copies have run.  BITSTACK_E_RANGE when every slot is taken. */
+int bitstack_push_block(bitstack_weight_t* w, const void* staging, bitstack_stream_t stream);
+
+/* Offloads the last loaded block: no device work, its slot is free for the next push.  Calls
+ * already enqueued that use the block must have finished before the slot is overwritten. */
+int bitstack_pop_block(bitstack_weight_t* w);
+
+/* Number of loaded blocks, and their bytes by Eq. (9): resident * bitstack_block_bytes. */
+int bitstack_resident_blocks(const bitstack_weight_t* w);
+size_t bitstack_resident_bytes(const bitstack_weight_t* w);
+
 /* The forward pass for one token (batch-1 decode):
  *   y = ( sum_{i < n_loaded} S_i (.) (U_i V_i^T) ) diag(1/s) x           (Eq. 4 + Eq. 8)
  *   x: device fp16 [in], 16-byte aligned.   y: device fp16 [out], 16-byte aligned.
- *   n_loaded in [0, n]: the loaded prefix of the stack; 0 gives y = 0.
+ *   n_loaded in [0, resident blocks]: the prefix of the stack to use; 0 gives y = 0.
  * Asynchronous: work is enqueued on stream and the call returns. */
 int bitstack_linear(const void* x, const bitstack_weight_t* blocks, int n_loaded,
                     void* y, bitstack_stream_t stream);

@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL,
     OPT_DECODE_KSLAB, OPT_DECODE_BGROUPS,
     block_bytes,
+    block_staging_bytes,
+    stage_block_host,
     lib,
     linear_many,
     make_jobs,

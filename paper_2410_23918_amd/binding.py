@@ -57,6 +57,20 @@ def lib():
     L.bitstack_set_option.argtypes = [i32, i32]
     L.bitstack_probe_read.argtypes = [vp, sz, vp, i32, vp]
     L.bitstack_probe_read.restype = i32
+    L.bitstack_block_staging_bytes.restype = sz
+    L.bitstack_block_staging_bytes.argtypes = [i32, i32, i32]
+    L.bitstack_stage_block_host.argtypes = [i32, i32, i32, vp, vp, vp, vp, sz]
+    L.bitstack_stage_block_host.restype = i32
+    L.bitstack_create_stack.argtypes = [i32, i32, i32, i32, i32, vp, vp, sz, vp, C.POINTER(vp)]
+    L.bitstack_create_stack.restype = i32
+    L.bitstack_push_block.argtypes = [vp, vp, vp]
+    L.bitstack_push_block.restype = i32
+    L.bitstack_pop_block.argtypes = [vp]
+    L.bitstack_pop_block.restype = i32
+    L.bitstack_resident_blocks.argtypes = [vp]
+    L.bitstack_resident_blocks.restype = i32
+    L.bitstack_resident_bytes.argtypes = [vp]
+    L.bitstack_resident_bytes.restype = sz
     L.bitstack_release.argtypes = [vp]
     L.bitstack_release.restype = None
     L.bitstack_strerror.restype = C.c_char_p
@@ -155,6 +169,28 @@ def pack_image_host(sign_words, U, V, s, max_batch: int = 1) -> np.ndarray:
     return img
 
 
+def block_staging_bytes(out: int, inn: int, k: int = 16) -> int:
+    return int(lib().bitstack_block_staging_bytes(out, inn, k))
+
+
+def stage_block_host(sign_words, U, V, staging: np.ndarray | None = None) -> np.ndarray:
+    """bitstack_stage_block_host: one block (canonical words [out][in/32], U [out][k], V [in][k]) in
+    device form, in `staging` (uint8 array, e.g. a view of pinned memory) or a new array."""
+    sw = np.ascontiguousarray(sign_words, dtype=np.uint32)
+    U = np.ascontiguousarray(U, dtype=np.float16)
+    V = np.ascontiguousarray(V, dtype=np.float16)
+    out, k = U.shape
+    inn = V.shape[0]
+    nbytes = block_staging_bytes(out, inn, k)
+    if nbytes == 0:
+        raise BitStackError(-2, "bitstack_block_staging_bytes")
+    if staging is None:
+        staging = np.empty(nbytes, dtype=np.uint8)
+    _check(lib().bitstack_stage_block_host(out, inn, k, _ptr(sw), _ptr(U), _ptr(V), _ptr(staging), staging.nbytes),
+           "bitstack_stage_block_host")
+    return staging
+
+
 def unpack_image_host(img: np.ndarray, out: int, inn: int, k: int, n: int, max_batch: int, block: int):
     sw = np.empty((out, inn // 32), dtype=np.uint32)
     U = np.empty((out, k), dtype=np.float16)
@@ -181,6 +217,45 @@ class PackedStack:
         _check(lib().bitstack_pack_blocks(out, inn, k, n, max_batch, _ptr(sw), _ptr(U), _ptr(V), _ptr(s),
                                           self.buf.data_ptr(), nbytes, st, C.byref(self._h)),
                "bitstack_pack_blocks")
+
+    @classmethod
+    def empty(cls, out: int, inn: int, n_slots: int, s, k: int = 16, max_batch: int = 1, device="cuda:0", stream=None):
+        """bitstack_create_stack: room for n_slots blocks, none loaded."""
+        import torch
+        self = cls.__new__(cls)
+        s = np.ascontiguousarray(s, dtype=np.float32)
+        self.out, self.inn, self.k, self.n, self.max_batch = out, inn, k, n_slots, max_batch
+        nbytes = packed_bytes(out, inn, k, n_slots, max_batch)
+        if nbytes == 0:
+            raise BitStackError(-2, "bitstack_packed_bytes")
+        self.device = torch.device(device)
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self._h = C.c_void_p()
+        self._staged = []
+        _check(lib().bitstack_create_stack(out, inn, k, n_slots, max_batch, _ptr(s), self.buf.data_ptr(), nbytes,
+                                           self._stream(stream), C.byref(self._h)), "bitstack_create_stack")
+        return self
+
+    def push_block(self, sign_words, U, V, stream=None):
+        """Stages the block in pinned host memory (kept alive here) and enqueues its load."""
+        import torch
+        pinned = torch.empty(block_staging_bytes(self.out, self.inn, self.k), dtype=torch.uint8, pin_memory=True)
+        stage_block_host(sign_words, U, V, pinned.numpy())
+        _check(lib().bitstack_push_block(self._h, pinned.data_ptr(), self._stream(stream)), "bitstack_push_block")
+        if not hasattr(self, "_staged"):
+            self._staged = []
+        self._staged.append(pinned)
+
+    def pop_block(self):
+        _check(lib().bitstack_pop_block(self._h), "bitstack_pop_block")
+
+    @property
+    def resident_blocks(self) -> int:
+        return int(lib().bitstack_resident_blocks(self._h))
+
+    @property
+    def resident_bytes(self) -> int:
+        return int(lib().bitstack_resident_bytes(self._h))
 
     def _stream(self, stream):
         import torch

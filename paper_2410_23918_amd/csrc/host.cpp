@@ -18,6 +18,7 @@ using namespace bitstack;
 struct bitstack_weight {
     Geometry geo;
     unsigned char* dev;  // caller-owned device buffer
+    int resident;        // blocks 0 .. resident-1 are loaded (Section 2.2: blocks come and go in stack order)
 };
 
 static thread_local int g_last_hip = 0;
@@ -69,6 +70,30 @@ static int check_pack_args(int out, int in, int k, int n, int max_batch, const u
     return BITSTACK_OK;
 }
 
+// device form of one block: sign tiles, V panels, U rows into blk (block_stride bytes), and the
+// derived per-channel maxima of V into vm (in values, panel order)
+static void pack_block(const Geometry& g, unsigned char* blk, uint16_t* vm, const uint32_t* csw, const uint16_t* cu,
+                       const uint16_t* cv) {
+    const int out = g.out, in = g.in, wpr = in / 32;
+    uint32_t* dsw = reinterpret_cast<uint32_t*>(blk);
+    for (int o = 0; o < out; ++o)
+        for (int w = 0; w < wpr; ++w) dsw[sign_word_index(in, o, w)] = csw[size_t(o) * wpr + w];
+    uint16_t* dv = reinterpret_cast<uint16_t*>(blk + g.off_v);
+    for (int j = 0; j < in; ++j)
+        for (int r = 0; r < kRank; ++r) dv[v_index(j, r)] = cv[size_t(j) * kRank + r];
+    std::memcpy(blk + g.off_u, cu, size_t(out) * kRank * 2);
+    // max_r |V[j][r]| per channel (fp16 magnitudes compare like their bit patterns)
+    for (int j = 0; j < in; ++j) {
+        uint16_t m = 0;
+        for (int r = 0; r < kRank; ++r) {
+            uint16_t a = cv[size_t(j) * kRank + r] & 0x7FFFu;
+            if (a > 0x7C00u) a = 0x7C00u;  // NaN payloads: treat as infinity
+            if (a > m) m = a;
+        }
+        vm[panel_index(j)] = m;
+    }
+}
+
 int bitstack_pack_image_host(int out, int in, int k, int n, int max_batch,
                              const uint32_t* sign_words, const uint16_t* U, const uint16_t* V,
                              const float* s, void* image, size_t image_bytes) {
@@ -82,29 +107,10 @@ int bitstack_pack_image_host(int out, int in, int k, int n, int max_batch,
     float* rs = reinterpret_cast<float*>(img + g.off_rs);
     for (int j = 0; j < in; ++j) rs[j] = 1.0f / s[j];
     const int wpr = in / 32;
-    for (int i = 0; i < n; ++i) {
-        unsigned char* blk = img + g.off_blocks + size_t(i) * g.block_stride;
-        uint32_t* dsw = reinterpret_cast<uint32_t*>(blk);
-        const uint32_t* csw = sign_words + size_t(i) * out * wpr;
-        for (int o = 0; o < out; ++o)
-            for (int w = 0; w < wpr; ++w) dsw[sign_word_index(in, o, w)] = csw[size_t(o) * wpr + w];
-        uint16_t* dv = reinterpret_cast<uint16_t*>(blk + g.off_v);
-        const uint16_t* cv = V + size_t(i) * in * kRank;
-        for (int j = 0; j < in; ++j)
-            for (int r = 0; r < kRank; ++r) dv[v_index(j, r)] = cv[size_t(j) * kRank + r];
-        std::memcpy(blk + g.off_u, U + size_t(i) * out * kRank, size_t(out) * kRank * 2);
-        // derived: max_r |V[j][r]| per channel (fp16 magnitudes compare like their bit patterns)
-        uint16_t* vm = reinterpret_cast<uint16_t*>(img + g.off_vmax) + size_t(i) * in;
-        for (int j = 0; j < in; ++j) {
-            uint16_t m = 0;
-            for (int r = 0; r < kRank; ++r) {
-                uint16_t a = cv[size_t(j) * kRank + r] & 0x7FFFu;
-                if (a > 0x7C00u) a = 0x7C00u;  // NaN payloads: treat as infinity
-                if (a > m) m = a;
-            }
-            vm[panel_index(j)] = m;
-        }
-    }
+    for (int i = 0; i < n; ++i)
+        pack_block(g, img + g.off_blocks + size_t(i) * g.block_stride,
+                   reinterpret_cast<uint16_t*>(img + g.off_vmax) + size_t(i) * in, sign_words + size_t(i) * out * wpr,
+                   U + size_t(i) * out * kRank, V + size_t(i) * in * kRank);
     return BITSTACK_OK;
 }
 
@@ -163,15 +169,91 @@ int bitstack_pack_blocks(int out, int in, int k, int n, int max_batch, const uin
     if (!w) return BITSTACK_E_BUFSIZE;
     w->geo = g;
     w->dev = static_cast<unsigned char*>(device_buf);
+    w->resident = n;
     *handle = w;
     return BITSTACK_OK;
+}
+
+// ---- dynamic loading: one block at a time (Section 2.2; appendix on minimal transmission units)
+
+size_t bitstack_block_staging_bytes(int out, int in, int k) {
+    if (!shape_ok(out, in, k)) return 0;
+    return align256(bitstack_block_bytes(out, in, k)) + align256(size_t(in) * 2);
+}
+
+int bitstack_stage_block_host(int out, int in, int k, const uint32_t* sign_words, const uint16_t* U,
+                              const uint16_t* V, void* staging, size_t staging_bytes) {
+    if (!shape_ok(out, in, k)) return BITSTACK_E_SHAPE;
+    if (!sign_words || !U || !V || !staging) return BITSTACK_E_NULL;
+    if (staging_bytes < bitstack_block_staging_bytes(out, in, k)) return BITSTACK_E_BUFSIZE;
+    const Geometry g = make_geometry(out, in, 1, 1);
+    unsigned char* st = static_cast<unsigned char*>(staging);
+    std::memset(st, 0, bitstack_block_staging_bytes(out, in, k));
+    pack_block(g, st, reinterpret_cast<uint16_t*>(st + align256(g.block_stride)), sign_words, U, V);
+    return BITSTACK_OK;
+}
+
+int bitstack_create_stack(int out, int in, int k, int n_slots, int max_batch, const float* s, void* device_buf,
+                          size_t device_buf_bytes, bitstack_stream_t stream, bitstack_weight_t** handle) {
+    if (!handle) return BITSTACK_E_NULL;
+    *handle = nullptr;
+    int rc = check_pack_args(out, in, k, 0, max_batch, nullptr, nullptr, nullptr, s);
+    if (rc) return rc;
+    if (n_slots < 1) return BITSTACK_E_RANGE;
+    if (!device_buf) return BITSTACK_E_NULL;
+    if (reinterpret_cast<uintptr_t>(device_buf) % 256) return BITSTACK_E_ALIGN;
+    const Geometry g = make_geometry(out, in, n_slots, max_batch);
+    if (device_buf_bytes < g.total) return BITSTACK_E_BUFSIZE;
+    std::vector<float> rs(in);
+    for (int j = 0; j < in; ++j) rs[j] = 1.0f / s[j];
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char* dev = static_cast<unsigned char*>(device_buf);
+    BS_HIP(hipMemcpyAsync(dev + g.off_rs, rs.data(), size_t(in) * 4, hipMemcpyHostToDevice, st));
+    // workspace and counters start at zero; block slots and row maxima are written by the pushes
+    BS_HIP(hipMemsetAsync(dev + g.off_part, 0, g.total - g.off_part, st));
+    BS_HIP(hipStreamSynchronize(st));
+    bitstack_weight* w = new (std::nothrow) bitstack_weight;
+    if (!w) return BITSTACK_E_BUFSIZE;
+    w->geo = g;
+    w->dev = dev;
+    w->resident = 0;
+    *handle = w;
+    return BITSTACK_OK;
+}
+
+int bitstack_push_block(bitstack_weight_t* w, const void* staging, bitstack_stream_t stream) {
+    if (!w || !staging) return BITSTACK_E_NULL;
+    const Geometry& g = w->geo;
+    if (w->resident >= g.n) return BITSTACK_E_RANGE;
+    const unsigned char* st = static_cast<const unsigned char*>(staging);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int i = w->resident;
+    BS_HIP(hipMemcpyAsync(w->dev + g.off_blocks + size_t(i) * g.block_stride, st, g.block_stride,
+                          hipMemcpyHostToDevice, hs));
+    BS_HIP(hipMemcpyAsync(w->dev + g.off_vmax + size_t(i) * g.in * 2, st + align256(g.block_stride), size_t(g.in) * 2,
+                          hipMemcpyHostToDevice, hs));
+    w->resident = i + 1;
+    return BITSTACK_OK;
+}
+
+int bitstack_pop_block(bitstack_weight_t* w) {
+    if (!w) return BITSTACK_E_NULL;
+    if (w->resident < 1) return BITSTACK_E_RANGE;
+    --w->resident;
+    return BITSTACK_OK;
+}
+
+int bitstack_resident_blocks(const bitstack_weight_t* w) { return w ? w->resident : BITSTACK_E_NULL; }
+
+size_t bitstack_resident_bytes(const bitstack_weight_t* w) {
+    return w ? size_t(w->resident) * w->geo.block_stride : 0;
 }
 
 int bitstack_unpack_blocks(const bitstack_weight_t* w, int block, uint32_t* sign_words, uint16_t* U,
                            uint16_t* V, bitstack_stream_t stream) {
     if (!w) return BITSTACK_E_NULL;
     const Geometry& g = w->geo;
-    if (block < 0 || block >= g.n) return BITSTACK_E_RANGE;
+    if (block < 0 || block >= w->resident) return BITSTACK_E_RANGE;
     std::vector<unsigned char> buf;
     try {
         buf.resize(g.block_stride);
@@ -200,7 +282,7 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w,
                            int y_dtype, int kernel, bitstack_stream_t stream) {
     if (!x || !w || !y) return BITSTACK_E_NULL;
     const Geometry& g = w->geo;
-    if (n_loaded < 0 || n_loaded > g.n || batch < 1 || batch > g.max_batch) return BITSTACK_E_RANGE;
+    if (n_loaded < 0 || n_loaded > w->resident || batch < 1 || batch > g.max_batch) return BITSTACK_E_RANGE;
     if (y_dtype != BITSTACK_Y_F16 && y_dtype != BITSTACK_Y_F32) return BITSTACK_E_ARG;
     if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16) return BITSTACK_E_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -303,7 +385,7 @@ static bool can_join(const bitstack_job_t* jobs, int first, int j) {
     if (!a.x || !a.blocks || !a.y || !b.x || !b.blocks || !b.y) return false;
     if (b.x != a.x || b.blocks->geo.in != a.blocks->geo.in) return false;
     if (b.blocks->geo.min_slab != a.blocks->geo.min_slab) return false;
-    if (b.n_loaded < 1 || b.n_loaded > b.blocks->geo.n || a.n_loaded < 1 || a.n_loaded > a.blocks->geo.n) return false;
+    if (b.n_loaded < 1 || b.n_loaded > b.blocks->resident || a.n_loaded < 1 || a.n_loaded > a.blocks->resident) return false;
     if (reinterpret_cast<uintptr_t>(b.x) % 16 || reinterpret_cast<uintptr_t>(b.y) % 16) return false;
     const char* x0 = static_cast<const char*>(a.x);
     const char* x1 = x0 + size_t(a.blocks->geo.in) * 2;

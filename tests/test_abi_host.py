@@ -109,3 +109,25 @@ def test_bench_sign_packing_matches_oracle():
     from oracle import bitstack_oracle as O
     b = bench.Blocks(96, 512, 3, 3)
     assert np.array_equal(b.sign_words(), O.Stack(b.S, b.U, b.V, b.s).sign_words())
+
+
+def test_staged_block_equals_its_slot_in_the_whole_image():
+    """Dynamic loading moves one block at a time: the staged form of block i must be byte for byte
+    what packing the whole stack puts into slot i (block bytes by Eq. 9, then the row maxima)."""
+    out, inn, n = 96, 768, 3
+    rng = W.rng_for(3, 7)
+    s = W.column_scales(rng, inn)
+    S, U, V = W.synthetic_blocks(rng, out, inn, n, 16, s, 0.02)
+    sw = np.stack([O.pack_signs(S[i]) for i in range(n)])
+    img = B.pack_image_host(sw, U, V, s, max_batch=2)
+    bb = B.block_bytes(out, inn, 16)
+    assert B.block_staging_bytes(out, inn, 16) == (bb + 255) // 256 * 256 + (inn * 2 + 255) // 256 * 256
+    off_blocks = (inn * 4 + 255) // 256 * 256
+    off_vmax = (off_blocks + n * bb + 255) // 256 * 256
+    for i in range(n):
+        st = B.stage_block_host(sw[i], U[i], V[i])
+        assert np.array_equal(st[:bb], img[off_blocks + i * bb: off_blocks + (i + 1) * bb])
+        vm_off = (bb + 255) // 256 * 256
+        assert np.array_equal(st[vm_off: vm_off + inn * 2], img[off_vmax + i * inn * 2: off_vmax + (i + 1) * inn * 2])
+    with pytest.raises(B.BitStackError):
+        B.stage_block_host(sw[0], U[0], V[0], np.empty(16, dtype=np.uint8))

@@ -189,6 +189,52 @@ def test_small_batch_column_split_repeatable(B):
         del ps
 
 
+def test_blocks_loaded_and_offloaded_one_at_a_time(B):
+    """Section 2.2's use case: a stack grows and shrinks block by block.  After every push the
+    forward pass over the resident prefix matches the oracle; a popped slot can be refilled with a
+    different block; asking for more blocks than are resident is an error; byte accounting follows
+    Eq. 9."""
+    import torch
+    out, inn, n = 1056, 1024, 5
+    st = synth_stack(3, out, inn, n)
+    other = synth_stack(3, out, inn, n, tag=9)
+    sw, sw_o = st.sign_words(), other.sign_words()
+    ps = B.PackedStack.empty(out, inn, 4, st.s, max_batch=3)
+    assert ps.resident_blocks == 0 and ps.resident_bytes == 0
+    x = acts(3, 3, inn)
+    y0 = _run(B, ps, x[:1], 0, B.KERNEL_AUTO)
+    assert not y0.any()
+    for i in range(4):
+        ps.push_block(sw[i], st.U[i], st.V[i])
+        assert ps.resident_blocks == i + 1 and ps.resident_bytes == (i + 1) * B.block_bytes(out, inn)
+        for b, kern in ((1, B.KERNEL_DECODE), (3, B.KERNEL_PANEL)):
+            y = _run(B, ps, x[:b], i + 1, kern)
+            err = O.relative_error(y, O.forward_dense(st, x[:b], i + 1))
+            print(f"push {i}: B={b} rel err {err:.2e}", flush=True)
+            assert err <= TOL
+    with pytest.raises(B.BitStackError):          # every slot is taken
+        ps.push_block(sw[4], st.U[4], st.V[4])
+    torch.cuda.synchronize()
+    ps.pop_block()
+    ps.pop_block()
+    assert ps.resident_blocks == 2
+    with pytest.raises(B.BitStackError):          # block 2 is not resident any more
+        ps.linear(_to_dev(x[0]), 3)
+    # refill the freed slots with blocks of another decomposition: a mixed stack
+    ps.push_block(sw_o[2], other.U[2], other.V[2])
+    ps.push_block(sw_o[3], other.U[3], other.V[3])
+    mixed = O.Stack(np.concatenate([st.S[:2], other.S[2:4]]), np.concatenate([st.U[:2], other.U[2:4]]),
+                    np.concatenate([st.V[:2], other.V[2:4]]), st.s)
+    y = _run(B, ps, x[:1], 4, B.KERNEL_DECODE)
+    assert O.relative_error(y, O.forward_dense(mixed, x[:1], 4)) <= TOL
+    sw2, U2, V2 = ps.unpack_block(3)
+    assert np.array_equal(sw2, sw_o[3]) and np.array_equal(U2.view(np.uint16), other.U[3].view(np.uint16))
+    while ps.resident_blocks:
+        ps.pop_block()
+    with pytest.raises(B.BitStackError):
+        ps.pop_block()
+
+
 def test_argument_errors_on_device(B):
     import torch
     st = synth_stack(3, 32, 256, 1)
