@@ -338,10 +338,14 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
                 unsigned qq[8];
 #pragma unroll
                 for (int e2 = 0; e2 < 8; ++e2) {
-                    const __half2 h = *reinterpret_cast<const __half2*>(&vw[e2]);
-                    v2s qv = __builtin_amdgcn_cvt_pknorm_i16(__low2float(h) * xf[2 * e2], __high2float(h) * xf[2 * e2 + 1]);
-                    qv += v2s{128, 128};  // high byte becomes round(q / 256), low byte q ^ 0x80
-                    qq[e2] = *reinterpret_cast<unsigned*>(&qv);
+                    typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+                    const h2v h = __builtin_bit_cast(h2v, vw[e2]);
+                    // + 128 (in units of the 16-bit code) rides along in the multiply-add that also converts
+                    // the fp16 factor: the high byte of q + 128 is round(q / 256), the low byte q ^ 0x80
+                    constexpr float kHalfByte = 128.0f / 32767.0f;
+                    const v2s qv = __builtin_amdgcn_cvt_pknorm_i16(__builtin_fmaf(float(h[0]), xf[2 * e2], kHalfByte),
+                                                                   __builtin_fmaf(float(h[1]), xf[2 * e2 + 1], kHalfByte));
+                    qq[e2] = __builtin_bit_cast(unsigned, qv);
                 }
                 v4i H, L;
                 int sH = 0, sL = 0;
