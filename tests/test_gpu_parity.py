@@ -235,6 +235,39 @@ def test_blocks_loaded_and_offloaded_one_at_a_time(B):
         ps.pop_block()
 
 
+def test_job_list_merging_rules(B):
+    """Jobs that read one x are merged four at a time; a stack that appears twice, an output that
+    overlaps x or another output, or a different input width end a group.  Whatever the grouping,
+    every job's output must equal that of its own single launch."""
+    import torch
+    stacks = [_pack(B, synth_stack(3, 160, 1024, 3, tag=t)) for t in range(6)]
+    wide = _pack(B, synth_stack(3, 96, 2048, 2, tag=7))
+    x = _to_dev(acts(3, 1, 1024)[0])
+    xw = _to_dev(acts(3, 1, 2048)[0])
+    big = torch.zeros(1024 + 160, dtype=torch.float16, device="cuda:0")
+    big[:1024] = x
+    ys = [torch.full((160,), float("nan"), dtype=torch.float16, device="cuda:0") for _ in range(9)]
+    yw = torch.full((96,), float("nan"), dtype=torch.float16, device="cuda:0")
+    items = [
+        (x, stacks[0], 3, ys[0]), (x, stacks[1], 2, ys[1]), (x, stacks[2], 3, ys[2]), (x, stacks[3], 1, ys[3]),
+        (x, stacks[4], 3, ys[4]),                      # fifth of a run: starts a new group
+        (x, stacks[4], 2, ys[5]),                      # same stack again: its workspace is taken
+        (x, stacks[5], 0, ys[6]),                      # empty prefix: y = 0, never merged
+        (xw, wide, 2, yw),                             # other input
+        (big[:1024], stacks[0], 3, big[1024:]),        # output right behind its input in one buffer: fine
+        (x, stacks[1], 3, ys[7]), (x, stacks[2], 3, ys[7]),   # two jobs writing one output: not merged, last wins
+    ]
+    B.linear_many(B.make_jobs(items))
+    torch.cuda.synchronize()
+    got = [it[3].clone() for it in items]
+    for k, (xi, ps, nl, y) in enumerate(items):
+        want = ps.linear(xi, nl)
+        torch.cuda.synchronize()
+        if k == 9:
+            continue                                   # overwritten by job 10
+        assert torch.equal(got[k], want), k
+
+
 def test_argument_errors_on_device(B):
     import torch
     st = synth_stack(3, 32, 256, 1)
