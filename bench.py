@@ -252,7 +252,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build targets one GPU; run with --gpus 1 "
-                 "(the path would shard by output rows, see DESIGN.md)")
+                 "(the path would shard by output rows, one slice of every block per GPU)")
 
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
