@@ -124,34 +124,51 @@ def cpu_baseline(blocks, x, n_loaded, block_stream_bytes, y_gpu, budget_s=12.0):
 
 def batch_table(B, torch, dev, n):
     """Batch path (row a6): forced batch kernels at the MLP shapes of configs 3 and 5, one packed
-    copy each, inputs resident.  Useful FLOP/s = 2 * out * in * tokens / time."""
+    copy each, inputs resident; for the prefill-sized batches also the materialising path
+    (restore to a dense fp16 scratch, then the dense product).  Useful FLOP/s = 2 * out * in *
+    tokens / time."""
     from workloads import synth as W
+
+    def timed(fn, reps):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
     rows = []
-    for cfg, (o, i), batches in ((3, (14336, 4096), (4, 16, 64)), (3, (4096, 14336), (16,)),
+    for cfg, (o, i), batches in ((3, (14336, 4096), (4, 16, 64, 512, 2048)), (3, (4096, 14336), (16,)),
                                  (5, (28672, 8192), (128, 2048))):
         st = build_stack(o, i, n, cfg)
         ps = B.PackedStack(st.sign_words(), st.U, st.V, st.s, max_batch=max(batches))
         del st
+        wd = torch.empty((o, i), dtype=torch.float16, device=dev) if max(batches) > 64 else None
         for b in batches:
             x = torch.from_numpy(W.activations(W.rng_for(cfg, 100, b, i), b, i)).to(dev)
             y = torch.empty((b, o), dtype=torch.float16, device=dev)
-            reps = 10 if b <= 64 else 3
-            for _ in range(2):
-                ps.linear_batched(x, n, y=y, kernel=B.KERNEL_PANEL)
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                ps.linear_batched(x, n, y=y, kernel=B.KERNEL_PANEL)
-            e1.record()
-            torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) * 1e3 / reps
+            us = timed(lambda: ps.linear_batched(x, n, y=y, kernel=B.KERNEL_PANEL), 10 if b <= 64 else 3)
             tf = 2.0 * o * i * b / us / 1e6
             kern = "k_fused" if b <= 64 else "k_xpack + k_tile"
             log(f"[bench] batch path {o}x{i} n={n} tokens={b} ({kern}): {us:.1f} us, {tf:.1f} useful TFLOP/s")
             rows.append({"shape": f"{o}x{i}", "tokens": b, "kernel": kern, "us": round(us, 1),
                          "useful_TFLOPs": round(tf, 2)})
-        del ps
+            if b > 64:
+                y2 = torch.empty_like(y)
+                um = timed(lambda: ps.linear_materialised(x, n, wd, y=y2), 3)
+                ur = timed(lambda: ps.restore_weight(n, wd), 3)
+                tfm = 2.0 * o * i * b / um / 1e6
+                diff = (y2.float() - y.float()).abs().max().item() / y.float().abs().max().item()
+                log(f"[bench] materialising path {o}x{i} n={n} tokens={b} (k_tile<restore> + k_xpack + k_gemm): "
+                    f"{um:.1f} us ({ur:.1f} us of it restoring), {tfm:.1f} useful TFLOP/s; "
+                    f"max |difference| to the batch kernel / max |y| = {diff:.1e}")
+                rows.append({"shape": f"{o}x{i}", "tokens": b, "kernel": "restore + k_gemm", "us": round(um, 1),
+                             "restore_us": round(ur, 1), "useful_TFLOPs": round(tfm, 2)})
+        del ps, wd
     return rows
 
 

@@ -197,6 +197,34 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* bl
                            int n_loaded, void* y, int y_dtype, int kernel,
                            bitstack_stream_t stream);
 
+/* The materialising path (appendix "Inference with BitStack models", throughput of the
+ * restoration levels: its level 2 restores the weight, then multiplies).  For prefill-sized
+ * batches it is faster than the kernels that rebuild weight tiles on chip, at the price of
+ * out x in x 2 bytes of scratch; one scratch buffer can serve every stack of a model.
+ *
+ * bitstack_restore_weight writes
+ *     w_dense[o][j] = ( sum_{i < n_loaded} S_i[o][j] * (U_i V_i^T)[o][j] ) / s[j]     (Eq. 8, Eq. 4)
+ * as fp16, row-major [out][in], summed in fp32 over the blocks and rounded once.
+ *   w_dense: device, caller-owned, 256-byte aligned, w_dense_bytes >= bitstack_dense_bytes(out, in)
+ *   (BITSTACK_E_BUFSIZE otherwise).  n_loaded in [0, min(resident blocks,
+ *   bitstack_restore_max_blocks())], 0 gives a zero matrix; BITSTACK_E_RANGE otherwise.
+ * bitstack_linear_dense computes y = x w_dense^T for x device fp16 [batch][in], y device
+ *   [batch][out] of y_dtype; `blocks` supplies the shape and the activation scratch, so its image
+ *   must have been packed with max_batch > 64 and batch <= max_batch (BITSTACK_E_RANGE otherwise).
+ *   w_dense must hold what bitstack_restore_weight wrote for a stack of the same shape.
+ * bitstack_linear_materialised is the two in sequence on one stream; all arguments are checked
+ *   before anything is enqueued.
+ * All three are asynchronous and allocate nothing. */
+size_t bitstack_dense_bytes(int out, int in);
+int bitstack_restore_max_blocks(void);
+int bitstack_restore_weight(const bitstack_weight_t* blocks, int n_loaded, void* w_dense,
+                            size_t w_dense_bytes, bitstack_stream_t stream);
+int bitstack_linear_dense(const void* x, int batch, const bitstack_weight_t* blocks,
+                          const void* w_dense, void* y, int y_dtype, bitstack_stream_t stream);
+int bitstack_linear_materialised(const void* x, int batch, const bitstack_weight_t* blocks,
+                                 int n_loaded, void* w_dense, size_t w_dense_bytes, void* y,
+                                 int y_dtype, bitstack_stream_t stream);
+
 /* Tuning hooks for benchmarks (process-wide, not thread-safe).  value 0 restores
  * the built-in choice.  Unknown options or unsupported values give BITSTACK_E_ARG
  * (at the next launch for values). */

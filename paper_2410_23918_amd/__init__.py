@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     OPT_DECODE_KSLAB, OPT_DECODE_BGROUPS,
     block_bytes,
     block_staging_bytes,
+    dense_bytes,
+    restore_max_blocks,
     stage_block_host,
     lib,
     linear_many,

@@ -71,6 +71,16 @@ def lib():
     L.bitstack_resident_blocks.restype = i32
     L.bitstack_resident_bytes.argtypes = [vp]
     L.bitstack_resident_bytes.restype = sz
+    L.bitstack_dense_bytes.restype = sz
+    L.bitstack_dense_bytes.argtypes = [i32, i32]
+    L.bitstack_restore_max_blocks.restype = i32
+    L.bitstack_restore_max_blocks.argtypes = []
+    L.bitstack_restore_weight.argtypes = [vp, i32, vp, sz, vp]
+    L.bitstack_restore_weight.restype = i32
+    L.bitstack_linear_dense.argtypes = [vp, i32, vp, vp, vp, i32, vp]
+    L.bitstack_linear_dense.restype = i32
+    L.bitstack_linear_materialised.argtypes = [vp, i32, vp, i32, vp, sz, vp, i32, vp]
+    L.bitstack_linear_materialised.restype = i32
     L.bitstack_release.argtypes = [vp]
     L.bitstack_release.restype = None
     L.bitstack_strerror.restype = C.c_char_p
@@ -167,6 +177,14 @@ def pack_image_host(sign_words, U, V, s, max_batch: int = 1) -> np.ndarray:
     _check(lib().bitstack_pack_image_host(out, inn, k, n, max_batch, _ptr(sw), _ptr(U), _ptr(V), _ptr(s),
                                           _ptr(img), nbytes), "bitstack_pack_image_host")
     return img
+
+
+def dense_bytes(out: int, inn: int) -> int:
+    return int(lib().bitstack_dense_bytes(out, inn))
+
+
+def restore_max_blocks() -> int:
+    return int(lib().bitstack_restore_max_blocks())
 
 
 def block_staging_bytes(out: int, inn: int, k: int = 16) -> int:
@@ -297,6 +315,38 @@ class PackedStack:
         yd = Y_F32 if out_dtype == torch.float32 else Y_F16
         _check(lib().bitstack_linear_select(x.data_ptr(), batch, self._h, n_loaded, y.data_ptr(), yd, kernel,
                                             self._stream(stream)), "bitstack_linear_select")
+        return y
+
+    def restore_weight(self, n_loaded: int, w_dense=None, stream=None):
+        """bitstack_restore_weight: the loaded prefix as a dense fp16 [out][in] matrix (1/s folded in)."""
+        import torch
+        if w_dense is None:
+            w_dense = torch.empty((self.out, self.inn), dtype=torch.float16, device=self.device)
+        _check(lib().bitstack_restore_weight(self._h, n_loaded, w_dense.data_ptr(),
+                                             w_dense.numel() * w_dense.element_size(), self._stream(stream)),
+               "bitstack_restore_weight")
+        return w_dense
+
+    def _y_for(self, x, y, out_dtype):
+        import torch
+        out_dtype = out_dtype or (y.dtype if y is not None else torch.float16)
+        if y is None:
+            y = torch.empty((x.shape[0], self.out), dtype=out_dtype, device=self.device)
+        return y, (Y_F32 if out_dtype == torch.float32 else Y_F16)
+
+    def linear_dense(self, x, w_dense, y=None, out_dtype=None, stream=None):
+        """bitstack_linear_dense: y = x w_dense^T with a weight restored earlier."""
+        y, yd = self._y_for(x, y, out_dtype)
+        _check(lib().bitstack_linear_dense(x.data_ptr(), x.shape[0], self._h, w_dense.data_ptr(), y.data_ptr(), yd,
+                                           self._stream(stream)), "bitstack_linear_dense")
+        return y
+
+    def linear_materialised(self, x, n_loaded: int, w_dense, y=None, out_dtype=None, stream=None):
+        """bitstack_linear_materialised: restore into w_dense, then the dense product."""
+        y, yd = self._y_for(x, y, out_dtype)
+        _check(lib().bitstack_linear_materialised(x.data_ptr(), x.shape[0], self._h, n_loaded, w_dense.data_ptr(),
+                                                  w_dense.numel() * w_dense.element_size(), y.data_ptr(), yd,
+                                                  self._stream(stream)), "bitstack_linear_materialised")
         return y
 
     def release(self):

@@ -357,6 +357,80 @@ int bitstack_linear(const void* x, const bitstack_weight_t* blocks, int n_loaded
     return bitstack_linear_select(x, 1, blocks, n_loaded, y, BITSTACK_Y_F16, BITSTACK_KERNEL_AUTO, stream);
 }
 
+size_t bitstack_dense_bytes(int out, int in) {
+    if (!shape_ok(out, in, kRank)) return 0;
+    return size_t(out) * size_t(in) * 2;
+}
+
+int bitstack_restore_max_blocks(void) { return restore_max_blocks(); }
+
+static int dense_args(const bitstack_weight_t* w, const void* w_dense, size_t w_dense_bytes, bool check_size) {
+    if (!w || !w_dense) return BITSTACK_E_NULL;
+    if (reinterpret_cast<uintptr_t>(w_dense) % 256) return BITSTACK_E_ALIGN;
+    if (check_size && w_dense_bytes < size_t(w->geo.out) * size_t(w->geo.in) * 2) return BITSTACK_E_BUFSIZE;
+    return BITSTACK_OK;
+}
+
+int bitstack_restore_weight(const bitstack_weight_t* w, int n_loaded, void* w_dense, size_t w_dense_bytes,
+                            bitstack_stream_t stream) {
+    int rc = dense_args(w, w_dense, w_dense_bytes, true);
+    if (rc) return rc;
+    if (n_loaded < 0 || n_loaded > w->resident || n_loaded > restore_max_blocks()) return BITSTACK_E_RANGE;
+    LaunchArgs a;
+    a.x = nullptr;
+    a.y = nullptr;
+    a.image = w->dev;
+    a.geo = w->geo;
+    a.batch = 1;
+    a.n_loaded = n_loaded;
+    a.y_f32 = false;
+    a.wdense = w_dense;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = n_loaded == 0 ? launch_dense_zero(a, st) : launch_restore(a, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return BITSTACK_OK;
+}
+
+int bitstack_linear_dense(const void* x, int batch, const bitstack_weight_t* w, const void* w_dense, void* y,
+                          int y_dtype, bitstack_stream_t stream) {
+    if (!x || !y) return BITSTACK_E_NULL;
+    int rc = dense_args(w, w_dense, 0, false);
+    if (rc) return rc;
+    const Geometry& g = w->geo;
+    if (batch < 1 || batch > g.max_batch || g.xpack_bytes == 0) return BITSTACK_E_RANGE;
+    if (y_dtype != BITSTACK_Y_F16 && y_dtype != BITSTACK_Y_F32) return BITSTACK_E_ARG;
+    if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16) return BITSTACK_E_ALIGN;
+    LaunchArgs a;
+    a.x = x;
+    a.y = y;
+    a.image = w->dev;
+    a.geo = g;
+    a.batch = batch;
+    a.n_loaded = 0;
+    a.y_f32 = (y_dtype == BITSTACK_Y_F32);
+    a.wdense = const_cast<void*>(w_dense);
+    hipError_t e = launch_dense(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return BITSTACK_OK;
+}
+
+int bitstack_linear_materialised(const void* x, int batch, const bitstack_weight_t* w, int n_loaded,
+                                 void* w_dense, size_t w_dense_bytes, void* y, int y_dtype,
+                                 bitstack_stream_t stream) {
+    if (!x || !y) return BITSTACK_E_NULL;
+    int rc = dense_args(w, w_dense, w_dense_bytes, true);
+    if (rc) return rc;
+    // every argument is checked before anything is enqueued
+    const Geometry& g = w->geo;
+    if (n_loaded < 0 || n_loaded > w->resident || n_loaded > restore_max_blocks()) return BITSTACK_E_RANGE;
+    if (batch < 1 || batch > g.max_batch || g.xpack_bytes == 0) return BITSTACK_E_RANGE;
+    if (y_dtype != BITSTACK_Y_F16 && y_dtype != BITSTACK_Y_F32) return BITSTACK_E_ARG;
+    if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16) return BITSTACK_E_ALIGN;
+    rc = bitstack_restore_weight(w, n_loaded, w_dense, w_dense_bytes, stream);
+    if (rc) return rc;
+    return bitstack_linear_dense(x, batch, w, w_dense, y, y_dtype, stream);
+}
+
 int bitstack_probe_read(const void* device_buf, size_t bytes, void* device_sink, int workgroups,
                         bitstack_stream_t stream) {
     if (!device_buf || !device_sink) return BITSTACK_E_NULL;

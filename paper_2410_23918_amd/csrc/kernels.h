@@ -14,6 +14,7 @@ struct LaunchArgs {
     int batch;
     int n_loaded;
     bool y_f32;
+    void* wdense = nullptr;  // device fp16 [out][in]: the restored weight of the materialising path
 };
 
 // Tunables of the decode kernel (0 = choose by shape).
@@ -30,6 +31,11 @@ hipError_t launch_decode(const LaunchArgs& a, hipStream_t st);
 // up to 4 batch-1 calls in one launch; all must use the same column slab (Geometry::min_slab)
 hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st);
 hipError_t launch_panel(const LaunchArgs& a, hipStream_t st);
+// materialising path: W' diag(1/s) of the loaded prefix -> a.wdense; then y = x wdense^T
+hipError_t launch_restore(const LaunchArgs& a, hipStream_t st);
+hipError_t launch_dense_zero(const LaunchArgs& a, hipStream_t st);
+hipError_t launch_dense(const LaunchArgs& a, hipStream_t st);
+int restore_max_blocks();
 // column split the small-batch kernel uses for this shape (1 = none)
 int small_batch_split(int out, int in, int batch, int part_slots);
 

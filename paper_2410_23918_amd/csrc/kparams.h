@@ -24,6 +24,7 @@ struct KParams {
     int n_rs, n_ks;       // row slabs, column slabs per block
     int y_f32;
     __half* xpack;        // activation scratch in fragment order (null if the image has none)
+    void* wdense;         // fp16 [out][in]: restored weight (materialising path only)
 };
 
 // Several decode calls that read the same activation vector, merged into one launch: workgroup
@@ -57,8 +58,12 @@ inline KParams make_params(const LaunchArgs& a) {
     p.n_rs = p.n_ks = 0;
     p.y_f32 = a.y_f32 ? 1 : 0;
     p.xpack = a.geo.xpack_bytes ? reinterpret_cast<__half*>(a.image + a.geo.off_xpack) : nullptr;
+    p.wdense = a.wdense;
     return p;
 }
+
+// p.x [batch][in] -> p.xpack in matrix-core fragment order (tokens padded with zeros to a multiple of 32)
+void launch_xpack(const KParams& p, hipStream_t st);
 
 __device__ __forceinline__ void store_y(const KParams& p, size_t idx, float v) {
     if (p.y_f32)

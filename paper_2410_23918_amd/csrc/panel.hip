@@ -620,10 +620,20 @@ __global__ __launch_bounds__(256) void k_xpack(const __half* x, __half* xp, int 
     *reinterpret_cast<uint4*>(xp + item * 8) = v;
 }
 
+void launch_xpack(const KParams& p, hipStream_t st) {
+    const size_t lanes = size_t((p.batch + 31) / 32) * (p.in / 16) * 64;
+    hipLaunchKernelGGL(k_xpack, dim3(unsigned((lanes + 255) / 256)), dim3(256), 0, st, p.x, p.xpack, p.batch, p.in);
+}
+
 constexpr int kTileFixedLds = 8 * 2 * kVPriv + 2 * kPanelRows * kPanelLd * 2;
 constexpr int kTileMaxBlocks = (160 * 1024 - kTileFixedLds) / 2048 - 1;
 constexpr int kTileTokens = 512;   // tokens per workgroup
 
+// kRestore: the same construction of the weight tile, but the parked tiles are copied to a dense
+// fp16 matrix W' diag(1/s) [out][in] in memory instead of being multiplied with activations (the
+// restoring step of the appendix on inference throughput, "level 2"); blockIdx.y then selects a
+// range of chunk pairs instead of a token tile.
+template <bool kRestore>
 __global__ __launch_bounds__(512) void k_tile(KParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -636,10 +646,14 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
     const int nch = p.in / kChunkCols;
     const int iters = (nch + 1) / 2;
     const int n = p.n_loaded;
-    const int total = iters * n;
+    const int its_per_wg = kRestore ? (iters + int(gridDim.y) - 1) / int(gridDim.y) : iters;
+    const int it_first = kRestore ? int(blockIdx.y) * its_per_wg : 0;
+    const int it_end = min(iters, it_first + its_per_wg);
+    if (it_first >= it_end) return;
+    const int total = (it_end - it_first) * n;
     const int rt0 = blockIdx.x * 2, nrt = p.out / kTileRows;
     const int rtc[2] = {min(rt0, nrt - 1), min(rt0 + 1, nrt - 1)};   // clamped for loads
-    const int tok_w = blockIdx.y * kTileTokens + wave * 64;           // my first token in the product stage
+    const int tok_w = kRestore ? 0 : blockIdx.y * kTileTokens + wave * 64;   // my first token in the product stage
 
     for (int idx = tid; idx < n * 128; idx += 512) {   // U rows of my 64 output rows, all blocks -> LDS
         const int i = idx >> 7, piece = idx & 127;
@@ -780,7 +794,16 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
                 }
             }
         lds_barrier();   // both tiles parked
-        if (tok_w < p.batch) {
+        if (kRestore) {
+            __half* const wd = static_cast<__half*>(p.wdense);
+            for (int idx = tid; idx < 2 * kPanelRows * 32; idx += 512) {   // 16-byte pieces, a row's 32 in a row
+                const int tm = idx >> 11, r = (idx >> 5) & 63, piece = idx & 31;
+                const int chc = 2 * it + tm, row = (rt0 + (r >> 5)) * kTileRows + (r & 31);
+                if (chc < nch && row < p.out)
+                    *reinterpret_cast<uint4*>(wd + size_t(row) * p.in + chc * kChunkCols + piece * 8) =
+                        *reinterpret_cast<const uint4*>(wt + (tm * kPanelRows + r) * kPanelLd + piece * 8);
+            }
+        } else if (tok_w < p.batch) {
             // fragments of my two token groups: [group][in / 16][64 lanes][8]
             const __half* xrow[2];
 #pragma unroll
@@ -824,7 +847,7 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
         lds_barrier();   // tiles free for the next pair of chunks
     };
 
-    Pos q = {0, 0};
+    Pos q = {it_first, 0};
     VIn vA = fetch_v(q);
     SIn sA = fetch_s(q);
     q = advance(q);
@@ -838,7 +861,7 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
     v8h vf0 = read_vf(0, 0), vf1 = read_vf(0, 1);
     __syncthreads();   // U cache complete
 
-    int ci = 0, it = 0;
+    int ci = 0, it = it_first;
 #define BS_TILE_STEP(S, CUR, NXT, FAR)                                                     \
     {                                                                                      \
         const v8h uf0 = read_u(ci, 0), uf1 = read_u(ci, 1);                                \
@@ -856,7 +879,7 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
         vf1 = vn1;                                                                         \
         if (++ci == n) {                                                                   \
             ci = 0;                                                                        \
-            if (it < iters) flush_and_multiply(it);                                        \
+            if (it < it_end) flush_and_multiply(it);                                       \
             ++it;                                                                          \
         }                                                                                  \
     }
@@ -868,6 +891,7 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
     }
 #undef BS_TILE_STEP
 
+    if (kRestore) return;
     // C[i = token][n = row]: lane (row ln), register v holds token 8*(v/4) + 4*hl + v%4 of the group
 #pragma unroll
     for (int rg = 0; rg < 2; ++rg)
@@ -887,18 +911,50 @@ static hipError_t launch_tile(const KParams& p, hipStream_t st) {
     const size_t smem = size_t(kTileFixedLds) + size_t(p.n_loaded) * 2048;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tile),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tile<false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                            kTileFixedLds + kTileMaxBlocks * 2048);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const size_t lanes = size_t((p.batch + 31) / 32) * (p.in / 16) * 64;
-    hipLaunchKernelGGL(k_xpack, dim3(unsigned((lanes + 255) / 256)), dim3(256), 0, st, p.x, p.xpack, p.batch, p.in);
+    launch_xpack(p, st);
     dim3 grid((p.out + 2 * kTileRows - 1) / (2 * kTileRows), (p.batch + kTileTokens - 1) / kTileTokens);
-    hipLaunchKernelGGL(k_tile, grid, dim3(512), smem, st, p);
+    hipLaunchKernelGGL(k_tile<false>, grid, dim3(512), smem, st, p);
     return hipGetLastError();
 }
+
+// W' diag(1/s) of the loaded prefix as a dense fp16 matrix [out][in] (row-major) at a.wdense.
+hipError_t launch_restore(const LaunchArgs& a, hipStream_t st) {
+    KParams p = make_params(a);
+    if (a.n_loaded < 1 || a.n_loaded > kTileMaxBlocks || p.wdense == nullptr) return hipErrorInvalidValue;
+    const size_t smem = size_t(kTileFixedLds) + size_t(p.n_loaded) * 2048;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tile<true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           kTileFixedLds + kTileMaxBlocks * 2048);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    // Column slices per row tile pair: few, long workgroups pay the fixed costs (copy of the U
+    // rows, first loads, ~3 us) less often, many short ones fill the last round of the 256
+    // compute units better.  Per chunk pair: ~0.9 us per block plus ~2.5 us for the flush.
+    const int iters = (p.in / kChunkCols + 1) / 2;
+    const int row_wgs = (p.out + 2 * kTileRows - 1) / (2 * kTileRows);
+    int slices = 1;
+    double best = 0.0;
+    for (int sl = 1; sl <= iters; sl *= 2) {
+        const int per = (iters + sl - 1) / sl;
+        const double t = double((row_wgs * sl + 255) / 256) * (per * (0.9 * p.n_loaded + 2.5) + 3.0);
+        if (sl == 1 || t < best) {
+            best = t;
+            slices = sl;
+        }
+    }
+    hipLaunchKernelGGL(k_tile<true>, dim3(row_wgs, slices), dim3(512), smem, st, p);
+    return hipGetLastError();
+}
+int restore_max_blocks() { return kTileMaxBlocks; }
 
 hipError_t launch_panel(const LaunchArgs& a, hipStream_t st) {
     KParams p = make_params(a);

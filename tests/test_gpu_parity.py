@@ -406,6 +406,99 @@ def test_cfg4_layer_through_one_native_call_with_merged_launches(B):
     synth_stack.cache_clear()
 
 
+# ------------------------------------------------------------------ materialising path
+@pytest.mark.parametrize("out,inn,n", [(1056, 768, 3), (96, 2048, 2), (64, 512, 29)])
+def test_restored_weight_matches_eq8(B, out, inn, n):
+    """The dense matrix the restore kernel writes against Eq. 8 with the scaling of Eq. 4 folded
+    into the columns, element by element: per output row, max_j |w - w_ref| / max_j |w_ref|
+    (the weight is rounded to fp16 once; every block's magnitudes once more before they are
+    summed in fp32)."""
+    import torch
+    st = synth_stack(3, out, inn, n)
+    ps = _pack(B, st, max_batch=65)
+    assert B.dense_bytes(out, inn) == out * inn * 2
+    guard = 512
+    buf = torch.full((out * inn + 2 * guard,), 7.0, dtype=torch.float16, device="cuda:0")
+    wd = buf[guard:guard + out * inn].view(out, inn)
+    assert wd.data_ptr() % 256 == 0
+    for nl in sorted({0, 1, n // 2 + 1, n}):
+        ps.restore_weight(nl, wd)
+        torch.cuda.synchronize()
+        got = wd.float().cpu().numpy().astype(np.float64)
+        ref = O.reconstruct_scaled(st, nl) / np.asarray(st.s, dtype=np.float64)[None, :]
+        if nl == 0:
+            assert not got.any()
+        else:
+            err = O.relative_error(got, ref)
+            print(f"{out}x{inn} restored weight n_loaded={nl}: {err:.2e}", flush=True)
+            assert err <= TOL
+        assert (buf[:guard] == 7.0).all() and (buf[guard + out * inn:] == 7.0).all()   # nothing written outside
+    assert B.restore_max_blocks() == 29
+
+
+@pytest.mark.parametrize("out,inn,n", [(1056, 768, 3), (96, 2048, 2)])
+def test_materialised_path_every_tile_variant(B, out, inn, n):
+    """Restore + dense product against the oracle for batches on both sides of the product
+    kernel's tiles (32-token fragments, 64 tokens per wavefront, 256 per workgroup), with ragged
+    row tiles (out not a multiple of 256) and both output types; the two-step form (restore
+    once, multiply many times) gives the same bits as the combined call."""
+    import torch
+    st = synth_stack(3, out, inn, n)
+    batches = (1, 31, 33, 64, 65, 255, 256, 257, 513)
+    ps = _pack(B, st, max_batch=max(batches))
+    x = acts(3, max(batches), inn)
+    ref = O.forward_dense(st, x, n)
+    wd = torch.empty((out, inn), dtype=torch.float16, device="cuda:0")
+    for b in batches:
+        xd = _to_dev(x[:b])
+        for dt in (torch.float16, torch.float32):
+            y = ps.linear_materialised(xd, n, wd, out_dtype=dt)
+            torch.cuda.synchronize()
+            assert y.shape == (b, out)
+            err = O.relative_error(y.float().cpu().numpy(), ref[:b])
+            print(f"{out}x{inn} materialised B={b} {dt}: {err:.2e}", flush=True)
+            assert err <= TOL
+            y2 = ps.linear_dense(xd, wd, out_dtype=dt)
+            torch.cuda.synchronize()
+            assert torch.equal(y, y2)
+    # a shorter prefix through the same scratch
+    y = ps.linear_materialised(_to_dev(x[:70]), 1, wd)
+    torch.cuda.synchronize()
+    err = O.relative_error(y.float().cpu().numpy(), O.forward_dense(st, x[:70], 1))
+    assert err <= TOL
+    y = ps.linear_materialised(_to_dev(x[:70]), 0, wd)
+    torch.cuda.synchronize()
+    assert not y.any()
+
+
+def test_materialised_path_argument_errors(B):
+    import torch
+    L = B.lib()
+    st = synth_stack(3, 64, 512, 30)
+    ps = _pack(B, st, max_batch=100)
+    small = _pack(B, st, max_batch=8)          # no activation scratch in this image
+    x = _to_dev(acts(3, 100, 512))
+    y = torch.empty((100, 64), dtype=torch.float16, device="cuda:0")
+    wd = torch.empty((64 * 512 + 64,), dtype=torch.float16, device="cuda:0")
+    nb = 64 * 512 * 2
+    vp = C.c_void_p
+    assert L.bitstack_restore_weight(ps.handle, 30, vp(wd.data_ptr()), nb, None) == -3      # taller than the U cache
+    assert L.bitstack_restore_weight(ps.handle, 31, vp(wd.data_ptr()), nb, None) == -3
+    assert L.bitstack_restore_weight(ps.handle, 2, vp(wd.data_ptr()), nb - 2, None) == -6
+    assert L.bitstack_restore_weight(ps.handle, 2, vp(wd.data_ptr() + 16), nb, None) == -4
+    assert L.bitstack_restore_weight(ps.handle, 2, None, nb, None) == -1
+    assert L.bitstack_linear_dense(vp(x.data_ptr()), 101, ps.handle, vp(wd.data_ptr()), vp(y.data_ptr()), 0, None) == -3
+    assert L.bitstack_linear_dense(vp(x.data_ptr()), 8, small.handle, vp(wd.data_ptr()), vp(y.data_ptr()), 0, None) == -3
+    assert L.bitstack_linear_dense(vp(x.data_ptr()), 8, ps.handle, vp(wd.data_ptr()), vp(y.data_ptr()), 5, None) == -8
+    assert L.bitstack_linear_materialised(vp(x.data_ptr()), 8, ps.handle, 2, vp(wd.data_ptr()), nb - 2,
+                                          vp(y.data_ptr()), 0, None) == -6
+    assert L.bitstack_linear_materialised(vp(x.data_ptr()), 8, ps.handle, 2, vp(wd.data_ptr()), nb,
+                                          vp(y.data_ptr()), 0, None) == 0
+    torch.cuda.synchronize()
+    err = O.relative_error(y[:8].float().cpu().numpy(), O.forward_dense(st, acts(3, 100, 512)[:8], 2))
+    assert err <= TOL
+
+
 # ------------------------------------------------------------------ config 5
 def test_cfg5_llama70b_mlp_prefill_sampled(B):
     """28672x8192, n=16, 2048 tokens.  The oracle cannot finish the full product in
@@ -439,4 +532,21 @@ def test_cfg5_llama70b_mlp_prefill_sampled(B):
     lin = np.abs(y3[0] + y3[1] - y3[2]).max() / np.abs(y3[2]).max()
     print(f"cfg5 linearity residual: {lin:.2e}", flush=True)
     assert lin <= 2 * TOL
+    # the materialising path on the same samples
+    wd = torch.empty((out, inn), dtype=torch.float16, device="cuda:0")
+    ym = ps.linear_materialised(xd, n, wd)
+    torch.cuda.synchronize()
+    gotm = ym[torch.from_numpy(toks).to("cuda:0")][:, torch.from_numpy(rows).to("cuda:0")].float().cpu().numpy()
+    errm = O.relative_error(gotm, ref)
+    print(f"cfg5 materialised, same samples: {errm:.2e}", flush=True)
+    assert errm <= TOL
+    assert torch.isfinite(ym).all() and (ym.abs().amax(dim=1) > 0).all()
+    wrows = wd[torch.from_numpy(rows).to("cuda:0")].float().cpu().numpy().astype(np.float64)
+    wref = np.zeros((len(rows), inn))
+    for i in range(n):
+        wref += st.S[i][rows].astype(np.float64) * (st.U[i][rows].astype(np.float64) @ st.V[i].astype(np.float64).T)
+    wref /= np.asarray(st.s, dtype=np.float64)[None, :]
+    errw = O.relative_error(wrows, wref)
+    print(f"cfg5 restored weight, 192 sampled rows: {errw:.2e}", flush=True)
+    assert errw <= TOL
     synth_stack.cache_clear()
