@@ -163,7 +163,7 @@ def batch_table(B, torch, dev, n):
                 ur = timed(lambda: ps.restore_weight(n, wd), 3)
                 tfm = 2.0 * o * i * b / um / 1e6
                 diff = (y2.float() - y.float()).abs().max().item() / y.float().abs().max().item()
-                log(f"[bench] materialising path {o}x{i} n={n} tokens={b} (k_tile<restore> + k_xpack + k_gemm): "
+                log(f"[bench] materialising path {o}x{i} n={n} tokens={b} (k_tile<restore> + k_gemm): "
                     f"{um:.1f} us ({ur:.1f} us of it restoring), {tfm:.1f} useful TFLOP/s; "
                     f"max |difference| to the batch kernel / max |y| = {diff:.1e}")
                 rows.append({"shape": f"{o}x{i}", "tokens": b, "kernel": "restore + k_gemm", "us": round(um, 1),

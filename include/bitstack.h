@@ -67,8 +67,10 @@ enum {
     BITSTACK_KERNEL_AUTO      = 0,
     BITSTACK_KERNEL_REFERENCE = 1, /* plain vector-ALU kernel, any batch <= max_batch            */
     BITSTACK_KERNEL_DECODE    = 2, /* matrix-core sign-stream kernel, one launch per token       */
-    BITSTACK_KERNEL_PANEL     = 3  /* batch kernels: weight rebuilt on chip (Eq. 8) and multiplied
+    BITSTACK_KERNEL_PANEL     = 3, /* batch kernels: weight rebuilt on chip (Eq. 8) and multiplied
                                       with the activations on the matrix cores, any batch        */
+    BITSTACK_KERNEL_MATERIALISE = 4 /* restore the weight to a dense scratch, then a dense product;
+                                       needs a scratch buffer: bitstack_linear_batched_ws only   */
 };
 
 /* Bytes of one residual block: (out*in + 16*k*(out+in)) / 8, Eq. (9) of the
@@ -209,14 +211,27 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* bl
  *   (BITSTACK_E_BUFSIZE otherwise).  n_loaded in [0, min(resident blocks,
  *   bitstack_restore_max_blocks())], 0 gives a zero matrix; BITSTACK_E_RANGE otherwise.
  * bitstack_linear_dense computes y = x w_dense^T for x device fp16 [batch][in], y device
- *   [batch][out] of y_dtype; `blocks` supplies the shape and the activation scratch, so its image
- *   must have been packed with max_batch > 64 and batch <= max_batch (BITSTACK_E_RANGE otherwise).
+ *   [batch][out] of y_dtype; `blocks` supplies the shape; 1 <= batch <= max_batch given at pack
+ *   time (BITSTACK_E_RANGE otherwise); x and w_dense below 4 GiB each.
  *   w_dense must hold what bitstack_restore_weight wrote for a stack of the same shape.
  * bitstack_linear_materialised is the two in sequence on one stream; all arguments are checked
  *   before anything is enqueued.
  * All three are asynchronous and allocate nothing. */
 size_t bitstack_dense_bytes(int out, int in);
 int bitstack_restore_max_blocks(void);
+
+/* bitstack_linear_batched with an optional scratch buffer (device, caller-owned, 256-byte
+ * aligned, may be NULL): when it holds at least bitstack_dense_bytes(out, in) bytes and the
+ * materialising path is estimated to be faster for this batch and stack height, that path is
+ * taken and overwrites the buffer; otherwise the buffer is left alone.  Same results contract and errors as bitstack_linear_batched.
+ * bitstack_choose_kernel (host only, no device work) returns the BITSTACK_KERNEL_* value that
+ * call would pick for a stack of this shape (BITSTACK_KERNEL_AUTO for n_loaded = 0, where y is
+ * only cleared), or a negative error code for an unsupported shape / out-of-range arguments. */
+int bitstack_linear_batched_ws(const void* x, int batch, const bitstack_weight_t* blocks,
+                               int n_loaded, void* y, int y_dtype, void* workspace,
+                               size_t workspace_bytes, bitstack_stream_t stream);
+int bitstack_choose_kernel(int out, int in, int n_slots, int max_batch, int batch, int n_loaded,
+                           size_t workspace_bytes);
 int bitstack_restore_weight(const bitstack_weight_t* blocks, int n_loaded, void* w_dense,
                             size_t w_dense_bytes, bitstack_stream_t stream);
 int bitstack_linear_dense(const void* x, int batch, const bitstack_weight_t* blocks,

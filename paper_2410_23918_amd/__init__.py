@@ -6,11 +6,12 @@ marshals arguments.  PyTorch supplies device memory and streams.
 from .binding import (  # noqa: F401
     BitStackError,
     PackedStack,
-    KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL,
+    KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL, KERNEL_MATERIALISE,
     OPT_DECODE_KSLAB, OPT_DECODE_BGROUPS,
     block_bytes,
     block_staging_bytes,
     dense_bytes,
+    choose_kernel,
     restore_max_blocks,
     stage_block_host,
     lib,

@@ -10,7 +10,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libbitstack.so")
 _lib = None
 
-KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL = 0, 1, 2, 3
+KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL, KERNEL_MATERIALISE = 0, 1, 2, 3, 4
 Y_F16, Y_F32 = 0, 1
 OPT_DECODE_KSLAB, OPT_DECODE_BGROUPS = 2, 3
 
@@ -81,6 +81,10 @@ def lib():
     L.bitstack_linear_dense.restype = i32
     L.bitstack_linear_materialised.argtypes = [vp, i32, vp, i32, vp, sz, vp, i32, vp]
     L.bitstack_linear_materialised.restype = i32
+    L.bitstack_linear_batched_ws.argtypes = [vp, i32, vp, i32, vp, i32, vp, sz, vp]
+    L.bitstack_linear_batched_ws.restype = i32
+    L.bitstack_choose_kernel.argtypes = [i32, i32, i32, i32, i32, i32, sz]
+    L.bitstack_choose_kernel.restype = i32
     L.bitstack_release.argtypes = [vp]
     L.bitstack_release.restype = None
     L.bitstack_strerror.restype = C.c_char_p
@@ -181,6 +185,14 @@ def pack_image_host(sign_words, U, V, s, max_batch: int = 1) -> np.ndarray:
 
 def dense_bytes(out: int, inn: int) -> int:
     return int(lib().bitstack_dense_bytes(out, inn))
+
+
+def choose_kernel(out: int, inn: int, n_slots: int, max_batch: int, batch: int, n_loaded: int,
+                  workspace_bytes: int = 0) -> int:
+    rc = int(lib().bitstack_choose_kernel(out, inn, n_slots, max_batch, batch, n_loaded, workspace_bytes))
+    if rc < 0:
+        raise BitStackError(rc, "bitstack_choose_kernel")
+    return rc
 
 
 def restore_max_blocks() -> int:
@@ -347,6 +359,15 @@ class PackedStack:
         _check(lib().bitstack_linear_materialised(x.data_ptr(), x.shape[0], self._h, n_loaded, w_dense.data_ptr(),
                                                   w_dense.numel() * w_dense.element_size(), y.data_ptr(), yd,
                                                   self._stream(stream)), "bitstack_linear_materialised")
+        return y
+
+    def linear_batched_ws(self, x, n_loaded: int, workspace=None, y=None, out_dtype=None, stream=None):
+        """bitstack_linear_batched_ws: kernel chosen by the library, scratch buffer optional."""
+        y, yd = self._y_for(x, y, out_dtype)
+        wp = workspace.data_ptr() if workspace is not None else None
+        wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+        _check(lib().bitstack_linear_batched_ws(x.data_ptr(), x.shape[0], self._h, n_loaded, y.data_ptr(), yd, wp, wb,
+                                                self._stream(stream)), "bitstack_linear_batched_ws")
         return y
 
     def release(self):

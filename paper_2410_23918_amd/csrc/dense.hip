@@ -8,12 +8,17 @@
 // element whatever the batch, so for prefill-sized batches this beats rebuilding weight tiles per
 // token tile; the price is out x in x 2 bytes of scratch, shared by all stacks of a model.
 //
-// k_gemm: one workgroup (8 wavefronts) owns 256 output rows x 256 tokens and walks the input
-// columns in chunks of 64.  The weight chunk (256 x 64) goes through LDS, double buffered, loaded
-// two chunks ahead into registers; the activations come straight from memory in fragment order
-// (k_xpack), requested four steps ahead.  A wavefront owns 128 rows x 64 tokens: per step of 16
-// columns it reads four weight fragments from LDS and two activation fragments from its ring and
-// issues eight v_mfma_f32_32x32x16_f16.  One LDS-only barrier per chunk.
+// k_gemm: one workgroup (8 wavefronts, two per SIMD) owns 256 output rows x 256 tokens and walks
+// the input columns in chunks of 64.  Both operand chunks (256 x 64 each, rows of the dense weight
+// and rows of x as they lie in memory) go through LDS, double buffered; every thread requests its
+// eight 16-byte pieces of a chunk two chunks before they are written to LDS, so all global loads
+// of a wavefront have the same, long time to arrive (loads return in order: one late load would
+// hold up every younger one).  A wavefront owns 128 rows x 64 tokens: per step of 16 columns it
+// reads four weight and two activation fragments from LDS (rows padded by 16 bytes, conflict-free
+// 128-bit reads) and issues eight v_mfma_f32_32x32x16_f16; the other wavefront of the SIMD covers
+// the read latency.  One LDS-only barrier per chunk.  The fp16 output tile is turned in LDS and
+// leaves in 16-byte pieces.  Workgroup ids map to tiles so that all token tiles of a row tile run
+// on one XCD (one L2 pulls that part of the weight).
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -30,9 +35,10 @@ constexpr int kGemmRows = 256;              // output rows per workgroup
 constexpr int kGemmTokens = 256;            // tokens per workgroup
 constexpr int kGemmKc = 64;                 // input columns per chunk
 constexpr int kGemmLd = kGemmKc + 8;        // fp16 per LDS row (+8: bank spread for 128-bit reads)
-constexpr int kGemmBuf = kGemmRows * kGemmLd;   // fp16 per buffer
-constexpr int kGemmLds = 2 * kGemmBuf * 2;  // bytes
-constexpr int kGemmPd = 4;                  // activation fragments are requested this many steps ahead
+constexpr int kGemmTile = 256 * kGemmLd;    // fp16 per operand tile
+constexpr int kGemmLds = 2 * 2 * kGemmTile * 2;   // bytes: two buffers x {weight tile, activation tile}
+constexpr int kGemmYLd = 256 + 8;           // fp16 per LDS row of the output tile
+static_assert(256 * kGemmYLd * 2 <= kGemmLds, "the output tile reuses the operand buffers");
 
 __global__ __launch_bounds__(256) void k_dense_zero(uint4* w, size_t n16) {
     const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
@@ -41,7 +47,8 @@ __global__ __launch_bounds__(256) void k_dense_zero(uint4* w, size_t n16) {
 
 __global__ __launch_bounds__(512) void k_gemm(KParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    _Float16* const wl = reinterpret_cast<_Float16*>(smem);   // [2][256][kGemmLd]
+    _Float16* const wl = reinterpret_cast<_Float16*>(smem);   // [buffer][256 rows][kGemmLd]
+    _Float16* const xl = wl + 2 * kGemmTile;                   // [buffer][256 tokens][kGemmLd]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hl = lane >> 5, ln = lane & 31;
@@ -53,46 +60,60 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int rt = xcd + 8 * (slot / ntt), tt = slot % ntt;
     if (rt >= nrt) return;
-    const int row0 = rt * kGemmRows, tok0 = tt * kGemmTokens + tg * 64;
+    const int row0 = rt * kGemmRows, tok0 = tt * kGemmTokens;
     const int nkc = p.in / kGemmKc;   // a multiple of 4
 
-    // activation fragments of my two token groups: [group][in / 16][64 lanes][8]
-    const int last_group = (p.batch - 1) / 32;
-    const _Float16* xg[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-        xg[t] = reinterpret_cast<const _Float16*>(p.xpack) +
-                (size_t(min(tok0 / 32 + t, last_group)) * (p.in / 16) * 64 + lane) * 8;
-    const int nks = p.in / 16;
-    auto xfrag = [&](int t, int ks) -> v8h {
-        return *reinterpret_cast<const v8h*>(xg[t] + size_t(min(ks, nks - 1)) * 512);
+    // both tiles of a chunk: thread (row tid/8 + 64 i, 16-byte piece tid%8), i = 0..3; rows and
+    // tokens past the end repeat the last one (computed, never stored)
+    const unsigned char* const wbase = reinterpret_cast<const unsigned char*>(p.wdense);
+    const unsigned char* const xbase = reinterpret_cast<const unsigned char*>(p.x);
+    // (scalar variables and macros on purpose: arrays or structs of 128 bytes of load results
+    // are left in scratch memory by the compiler here)
+    auto off_of = [&](int first, int i, int limit) -> unsigned {
+        return unsigned((size_t(min(first + (tid >> 3) + 64 * i, limit - 1)) * p.in + (tid & 7) * 8) * 2);
     };
-
-    // weight chunk: thread (row tid/8 + 64 i, 16-byte piece tid%8), i = 0..3
-    const _Float16* const wd = reinterpret_cast<const _Float16*>(p.wdense);
-    const _Float16* wsrc[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-        wsrc[i] = wd + size_t(min(row0 + (tid >> 3) + 64 * i, p.out - 1)) * p.in + (tid & 7) * 8;
-    _Float16* const wdst = wl + (tid >> 3) * kGemmLd + (tid & 7) * 8;
-    struct WIn {
-        uint4 v[4];
+    const unsigned wo0 = off_of(row0, 0, p.out), wo1 = off_of(row0, 1, p.out), wo2 = off_of(row0, 2, p.out),
+                   wo3 = off_of(row0, 3, p.out);
+    const unsigned xo0 = off_of(tok0, 0, p.batch), xo1 = off_of(tok0, 1, p.batch), xo2 = off_of(tok0, 2, p.batch),
+                   xo3 = off_of(tok0, 3, p.batch);
+    const int dst = (tid >> 3) * kGemmLd + (tid & 7) * 8;
+    auto ld16 = [&](const unsigned char* base, unsigned off) -> uint4 {
+        return *reinterpret_cast<const uint4*>(base + off);
     };
-    auto load_w = [&](int kc) -> WIn {
-        WIn w;
-        const int c = min(kc, nkc - 1) * kGemmKc;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) w.v[i] = *reinterpret_cast<const uint4*>(wsrc[i] + c);
-        return w;
+    auto st16 = [&](_Float16* tile, int buf, int i, uint4 v) {
+        *reinterpret_cast<uint4*>(tile + buf * kGemmTile + dst + 64 * i * kGemmLd) = v;
     };
-    auto write_w = [&](const WIn& w, int buf) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(wdst + buf * kGemmBuf + 64 * i * kGemmLd) = w.v[i];
-    };
-    // fragment j (32 rows) of my 128 rows, step s (16 columns) of the chunk in buffer buf
+#define BS_GEMM_LOAD(S, KC)                                                                \
+    {                                                                                      \
+        const unsigned c = unsigned(min((KC), nkc - 1)) * (kGemmKc * 2);                   \
+        w##S##0 = ld16(wbase, wo0 + c);                                                    \
+        w##S##1 = ld16(wbase, wo1 + c);                                                    \
+        w##S##2 = ld16(wbase, wo2 + c);                                                    \
+        w##S##3 = ld16(wbase, wo3 + c);                                                    \
+        x##S##0 = ld16(xbase, xo0 + c);                                                    \
+        x##S##1 = ld16(xbase, xo1 + c);                                                    \
+        x##S##2 = ld16(xbase, xo2 + c);                                                    \
+        x##S##3 = ld16(xbase, xo3 + c);                                                    \
+    }
+#define BS_GEMM_WRITE(S, BUF)                                                              \
+    {                                                                                      \
+        st16(wl, BUF, 0, w##S##0);                                                         \
+        st16(wl, BUF, 1, w##S##1);                                                         \
+        st16(wl, BUF, 2, w##S##2);                                                         \
+        st16(wl, BUF, 3, w##S##3);                                                         \
+        st16(xl, BUF, 0, x##S##0);                                                         \
+        st16(xl, BUF, 1, x##S##1);                                                         \
+        st16(xl, BUF, 2, x##S##2);                                                         \
+        st16(xl, BUF, 3, x##S##3);                                                         \
+    }
+    // fragments of step s (16 columns) of the chunk in buffer buf: weight rows j*32.., tokens t*32..
     const _Float16* const wfr = wl + (rg * 128 + ln) * kGemmLd + 8 * hl;
+    const _Float16* const xfr = xl + (tg * 64 + ln) * kGemmLd + 8 * hl;
     auto wfrag = [&](int buf, int s, int j) -> v8h {
-        return *reinterpret_cast<const v8h*>(wfr + buf * kGemmBuf + j * 32 * kGemmLd + s * 16);
+        return *reinterpret_cast<const v8h*>(wfr + buf * kGemmTile + j * 32 * kGemmLd + s * 16);
+    };
+    auto xfrag = [&](int buf, int s, int t) -> v8h {
+        return *reinterpret_cast<const v8h*>(xfr + buf * kGemmTile + t * 32 * kGemmLd + s * 16);
     };
 
     v16f acc[4][2];   // [row fragment][token group]
@@ -103,67 +124,80 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][t][v] = 0.0f;
 
-    WIn wA = load_w(0);
-    WIn wB = load_w(1);
-    v8h ring[kGemmPd][2];
-#pragma unroll
-    for (int k = 0; k < kGemmPd; ++k) {
-        ring[k][0] = xfrag(0, k);
-        ring[k][1] = xfrag(1, k);
-    }
-    write_w(wA, 0);
-    wA = load_w(2);
+    uint4 wA0, wA1, wA2, wA3, xA0, xA1, xA2, xA3, wB0, wB1, wB2, wB3, xB0, xB1, xB2, xB3;
+    BS_GEMM_LOAD(A, 0)
+    BS_GEMM_LOAD(B, 1)
+    BS_GEMM_WRITE(A, 0)
+    BS_GEMM_LOAD(A, 2)
     lds_barrier();
-    v8h b[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) b[j] = wfrag(0, 0, j);
 
-    // One chunk from buffer BUF: at step 1 the chunk after it (already in registers W) goes to the
-    // other buffer and the chunk two further on is requested; the barrier after step 2 makes the
-    // other buffer readable for the prefetch at step 3 and protects this buffer from the next
-    // chunk's writes.
-#define BS_GEMM_CHUNK(KC, BUF, W)                                                          \
+    // One chunk from buffer BUF: at step 1 the chunk after it (already in registers T) goes to the
+    // other buffer and the chunk two further on is requested, so every global load has two chunks
+    // to arrive.  The barrier at the end makes the other buffer readable and protects this one
+    // from the writes of the chunk after next.  Fragments are read at the start of their step;
+    // the second wavefront of the SIMD covers that latency.
+#define BS_GEMM_CHUNK(KC, BUF, S)                                                          \
     {                                                                                      \
         _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                    \
-            const int ks = (KC) * 4 + s;                                                   \
-            const v8h a0 = ring[s][0], a1 = ring[s][1];                                    \
-            ring[s][0] = xfrag(0, ks + kGemmPd);                                           \
-            ring[s][1] = xfrag(1, ks + kGemmPd);                                           \
             if (s == 1) {                                                                  \
-                write_w(W, (BUF) ^ 1);                                                     \
-                W = load_w((KC) + 3);                                                      \
+                BS_GEMM_WRITE(S, (BUF) ^ 1)                                                \
+                BS_GEMM_LOAD(S, (KC) + 3)                                                  \
             }                                                                              \
-            __builtin_amdgcn_sched_barrier(0); /* keep the requests ahead of the step's arithmetic */ \
-            v8h nb[4];                                                                     \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j)                                  \
-                nb[j] = (s < 3) ? wfrag(BUF, s + 1, j) : wfrag((BUF) ^ 1, 0, j);           \
+            v8h b[4], a[2];                                                                \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) b[j] = wfrag(BUF, s, j);         \
+            _Pragma("unroll") for (int t = 0; t < 2; ++t) a[t] = xfrag(BUF, s, t);         \
+            __builtin_amdgcn_sched_barrier(0); /* requests before the step's arithmetic */ \
             _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                \
-                acc[j][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, b[j], acc[j][0], 0, 0, 0); \
-                acc[j][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b[j], acc[j][1], 0, 0, 0); \
+                acc[j][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], b[j], acc[j][0], 0, 0, 0); \
+                acc[j][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[1], b[j], acc[j][1], 0, 0, 0); \
             }                                                                              \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j) b[j] = nb[j];                    \
-            if (s == 2) lds_barrier();                                                     \
             __builtin_amdgcn_sched_barrier(0);                                             \
         }                                                                                  \
+        lds_barrier();                                                                     \
     }
-    static_assert(kGemmPd == 4, "the ring is indexed by the step inside a chunk");
     for (int kc = 0; kc < nkc; kc += 2) {
-        BS_GEMM_CHUNK(kc, 0, wB)
-        BS_GEMM_CHUNK(kc + 1, 1, wA)
+        BS_GEMM_CHUNK(kc, 0, B)
+        BS_GEMM_CHUNK(kc + 1, 1, A)
     }
 #undef BS_GEMM_CHUNK
+#undef BS_GEMM_LOAD
+#undef BS_GEMM_WRITE
 
     // C[i = token][n = row]: lane (row ln), register v holds token 8*(v/4) + 4*hl + v%4 of the group
+    if (p.y_f32) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int tok = tok0 + tg * 64 + t * 32 + 8 * (v >> 2) + 4 * hl + (v & 3);
+                    const int row = row0 + rg * 128 + j * 32 + ln;
+                    if (tok < p.batch && row < p.out) static_cast<float*>(p.y)[size_t(tok) * p.out + row] = acc[j][t][v];
+                }
+        return;
+    }
+    // fp16 output: the tile is turned in LDS (the operand buffers are free now; the loop's last
+    // barrier has passed) so that it leaves in 16-byte pieces, 512 contiguous bytes per token,
+    // instead of 2-byte pieces
+    _Float16* const yl = reinterpret_cast<_Float16*>(smem);   // [256 tokens][kGemmYLd]
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int tok = tok0 + t * 32 + 8 * (v >> 2) + 4 * hl + (v & 3);
-                const int row = row0 + rg * 128 + j * 32 + ln;
-                if (tok < p.batch && row < p.out) store_y(p, size_t(tok) * p.out + row, acc[j][t][v]);
-            }
+            for (int v = 0; v < 16; ++v)
+                yl[(tg * 64 + t * 32 + 8 * (v >> 2) + 4 * hl + (v & 3)) * kGemmYLd + rg * 128 + j * 32 + ln] =
+                    _Float16(acc[j][t][v]);
+    lds_barrier();
+    __half* const y = static_cast<__half*>(p.y);
+#pragma unroll 4
+    for (int k = 0; k < 16; ++k) {
+        const int idx = tid + 512 * k, tok = idx >> 5, piece = idx & 31;
+        const uint4 v = *reinterpret_cast<const uint4*>(yl + tok * kGemmYLd + piece * 8);
+        if (tok0 + tok < p.batch && row0 + piece * 8 < p.out)
+            *reinterpret_cast<uint4*>(y + size_t(tok0 + tok) * p.out + row0 + piece * 8) = v;
+    }
 }
 
 hipError_t launch_dense_zero(const LaunchArgs& a, hipStream_t st) {
@@ -175,7 +209,9 @@ hipError_t launch_dense_zero(const LaunchArgs& a, hipStream_t st) {
 
 hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {
     KParams p = make_params(a);
-    if (a.batch < 1 || p.xpack == nullptr || p.wdense == nullptr) return hipErrorInvalidValue;
+    if (a.batch < 1 || p.wdense == nullptr) return hipErrorInvalidValue;
+    if (size_t(p.batch) * p.in * 2 > 0xffffffffull || size_t(p.out) * p.in * 2 > 0xffffffffull)
+        return hipErrorInvalidValue;   // 32-bit byte offsets into x and the dense weight
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm),
@@ -183,7 +219,6 @@ hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    launch_xpack(p, st);
     const int ntt = (p.batch + kGemmTokens - 1) / kGemmTokens, nrt = (p.out + kGemmRows - 1) / kGemmRows;
     const unsigned wgs = unsigned(8 * ((nrt + 7) / 8) * ntt);
     hipLaunchKernelGGL(k_gemm, dim3(wgs), dim3(512), kGemmLds, st, p);

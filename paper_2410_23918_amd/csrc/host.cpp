@@ -278,13 +278,57 @@ int bitstack_weight_shape(const bitstack_weight_t* w, int* out, int* in, int* k,
     return BITSTACK_OK;
 }
 
-int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w, int n_loaded, void* y,
-                           int y_dtype, int kernel, bitstack_stream_t stream) {
+// Which kernel serves (batch, n_loaded) fastest.  Per-token decode launches stream the blocks
+// once per token.  The batch path has two kernels: up to 64 tokens, signed tiles are rebuilt per
+// group of 32 tokens; beyond that a weight tile is rebuilt once per 512 tokens and multiplied
+// with them.  Both take ~1 us per block and pair of 256-column chunks of a 64-row tile, the
+// second another ~13 us per chunk pair for the product.  With a scratch buffer for the dense
+// weight, restoring it once (~6.1e6 weight elements x blocks per us) and one dense product
+// (256 x 256 tiles, ~0.035 us per input column each) wins for prefill-sized batches.  Rates
+// measured on MI355X; decode: ~2.4 GB/ms of block stream plus ~15 us per launch.
+static int choose_kernel(const Geometry& g, int batch, int n_loaded, size_t workspace_bytes) {
+    if (batch == 1) return BITSTACK_KERNEL_DECODE;
+    const double blk_bytes = double(g.block_stride);
+    const double t_decode = batch * (15.0 + n_loaded * blk_bytes / 2.4e6);
+    const int row_tiles = (g.out + 63) / 64;
+    const int chunk_pairs = (g.in / 256 + 1) / 2;
+    double t_panel;
+    if (batch <= 64) {
+        const int split = small_batch_split(g.out, g.in, batch, g.part_slots);
+        const int wgs = row_tiles * ((batch + 31) / 32) * split;
+        t_panel = ((wgs + 255) / 256) * (15.0 + 1.0 * n_loaded * ((chunk_pairs + split - 1) / split)) + (split > 1 ? 5.0 : 0.0);
+    } else {
+        // up to 256 tokens only one wavefront per SIMD has tokens to multiply: half the product time
+        const int wgs = row_tiles * ((batch + 511) / 512);
+        const double rounds = wgs <= 256 ? 1.0 : wgs / 256.0;   // later workgroups start as earlier ones end
+        t_panel = rounds * (15.0 + chunk_pairs * (1.0 * n_loaded + (batch > 256 ? 13.0 : 6.5)));
+    }
+    int kernel = t_decode <= t_panel ? BITSTACK_KERNEL_DECODE : BITSTACK_KERNEL_PANEL;
+    const double t_best = t_decode <= t_panel ? t_decode : t_panel;
+    if (n_loaded <= restore_max_blocks() && workspace_bytes >= size_t(g.out) * size_t(g.in) * 2) {
+        const int wgs = ((g.out + 255) / 256) * ((batch + 255) / 256);
+        const double t_mat = 10.0 + double(g.out) * g.in * n_loaded / 6.1e6 + 10.0 + ((wgs + 255) / 256) * 0.035 * g.in;
+        if (t_mat < t_best) kernel = BITSTACK_KERNEL_MATERIALISE;
+    }
+    return kernel;
+}
+
+int bitstack_choose_kernel(int out, int in, int n_slots, int max_batch, int batch, int n_loaded,
+                           size_t workspace_bytes) {
+    if (!shape_ok(out, in, kRank) || n_slots < 0 || max_batch < 1) return BITSTACK_E_SHAPE;
+    if (batch < 1 || batch > max_batch || n_loaded < 0 || n_loaded > n_slots) return BITSTACK_E_RANGE;
+    if (n_loaded == 0) return BITSTACK_KERNEL_AUTO;   // nothing to choose: y is cleared
+    return choose_kernel(make_geometry(out, in, n_slots, max_batch), batch, n_loaded, workspace_bytes);
+}
+
+static int linear_impl(const void* x, int batch, const bitstack_weight_t* w, int n_loaded, void* y, int y_dtype,
+                       int kernel, void* workspace, size_t workspace_bytes, bitstack_stream_t stream) {
     if (!x || !w || !y) return BITSTACK_E_NULL;
     const Geometry& g = w->geo;
     if (n_loaded < 0 || n_loaded > w->resident || batch < 1 || batch > g.max_batch) return BITSTACK_E_RANGE;
     if (y_dtype != BITSTACK_Y_F16 && y_dtype != BITSTACK_Y_F32) return BITSTACK_E_ARG;
     if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16) return BITSTACK_E_ALIGN;
+    if (workspace && reinterpret_cast<uintptr_t>(workspace) % 256) return BITSTACK_E_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
     LaunchArgs a;
     a.x = x;
@@ -298,28 +342,7 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w,
     if (n_loaded == 0) {
         e = launch_zero(a, st);
     } else {
-        if (kernel == BITSTACK_KERNEL_AUTO) {
-            // Per-token decode launches stream the blocks once per token.  The batch path has two
-            // kernels: up to 64 tokens, signed tiles are rebuilt per group of 32 tokens; beyond
-            // that a weight tile is rebuilt once per 512 tokens and multiplied with them.  Both
-            // take ~1 us per block and pair of 256-column chunks of a 64-row tile, the second
-            // another ~13 us per chunk pair for the product.  Rates measured on MI355X; decode:
-            // ~2.4 GB/ms of block stream plus ~15 us per launch.
-            const double blk_bytes = double(g.block_stride);
-            const double t_decode = batch * (15.0 + n_loaded * blk_bytes / 2.4e6);
-            const int row_tiles = (g.out + 63) / 64;
-            const int chunk_pairs = (g.in / 256 + 1) / 2;
-            double t_panel;
-            if (batch <= 64) {
-                const int split = small_batch_split(g.out, g.in, batch, g.part_slots);
-                const int wgs = row_tiles * ((batch + 31) / 32) * split;
-                t_panel = ((wgs + 255) / 256) * (15.0 + 1.0 * n_loaded * ((chunk_pairs + split - 1) / split)) + (split > 1 ? 5.0 : 0.0);
-            } else {
-                const int wgs = row_tiles * ((batch + 511) / 512);
-                t_panel = ((wgs + 255) / 256) * (15.0 + chunk_pairs * (1.0 * n_loaded + 13.0));
-            }
-            kernel = (batch == 1 || t_decode <= t_panel) ? BITSTACK_KERNEL_DECODE : BITSTACK_KERNEL_PANEL;
-        }
+        if (kernel == BITSTACK_KERNEL_AUTO) kernel = choose_kernel(g, batch, n_loaded, workspace ? workspace_bytes : 0);
         switch (kernel) {
             case BITSTACK_KERNEL_REFERENCE:
                 e = launch_reference(a, st);
@@ -339,12 +362,26 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w,
             case BITSTACK_KERNEL_PANEL:
                 e = launch_panel(a, st);
                 break;
+            case BITSTACK_KERNEL_MATERIALISE:
+                return bitstack_linear_materialised(x, batch, w, n_loaded, workspace, workspace ? workspace_bytes : 0, y,
+                                                    y_dtype, stream);
             default:
                 return BITSTACK_E_ARG;
         }
     }
     if (e != hipSuccess) return hip_fail(e);
     return BITSTACK_OK;
+}
+
+int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w, int n_loaded, void* y,
+                           int y_dtype, int kernel, bitstack_stream_t stream) {
+    if (kernel == BITSTACK_KERNEL_MATERIALISE) return BITSTACK_E_ARG;   // needs a scratch buffer: bitstack_linear_batched_ws
+    return linear_impl(x, batch, w, n_loaded, y, y_dtype, kernel, nullptr, 0, stream);
+}
+
+int bitstack_linear_batched_ws(const void* x, int batch, const bitstack_weight_t* w, int n_loaded, void* y,
+                               int y_dtype, void* workspace, size_t workspace_bytes, bitstack_stream_t stream) {
+    return linear_impl(x, batch, w, n_loaded, y, y_dtype, BITSTACK_KERNEL_AUTO, workspace, workspace_bytes, stream);
 }
 
 int bitstack_linear_batched(const void* x, int batch, const bitstack_weight_t* w, int n_loaded, void* y,
@@ -397,7 +434,7 @@ int bitstack_linear_dense(const void* x, int batch, const bitstack_weight_t* w, 
     int rc = dense_args(w, w_dense, 0, false);
     if (rc) return rc;
     const Geometry& g = w->geo;
-    if (batch < 1 || batch > g.max_batch || g.xpack_bytes == 0) return BITSTACK_E_RANGE;
+    if (batch < 1 || batch > g.max_batch) return BITSTACK_E_RANGE;
     if (y_dtype != BITSTACK_Y_F16 && y_dtype != BITSTACK_Y_F32) return BITSTACK_E_ARG;
     if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16) return BITSTACK_E_ALIGN;
     LaunchArgs a;
@@ -423,7 +460,7 @@ int bitstack_linear_materialised(const void* x, int batch, const bitstack_weight
     // every argument is checked before anything is enqueued
     const Geometry& g = w->geo;
     if (n_loaded < 0 || n_loaded > w->resident || n_loaded > restore_max_blocks()) return BITSTACK_E_RANGE;
-    if (batch < 1 || batch > g.max_batch || g.xpack_bytes == 0) return BITSTACK_E_RANGE;
+    if (batch < 1 || batch > g.max_batch) return BITSTACK_E_RANGE;
     if (y_dtype != BITSTACK_Y_F16 && y_dtype != BITSTACK_Y_F32) return BITSTACK_E_ARG;
     if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16) return BITSTACK_E_ALIGN;
     rc = bitstack_restore_weight(w, n_loaded, w_dense, w_dense_bytes, stream);

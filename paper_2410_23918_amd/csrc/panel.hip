@@ -740,37 +740,42 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
 
     // first = the chunk's first block: the accumulator starts from zero instead of being cleared
     // beforehand, so that its 64 registers are free during the product stage
-    auto rebuild = [&](auto first, const SIn& sg, v8h uf0, v8h uf1, v8h vf0, v8h vf1) {
+    auto magnitude = [&](int tb, v8h uf0, v8h uf1, v8h vf0, v8h vf1) -> v16f {
+        v16f z;
 #pragma unroll
-        for (int tile = 0; tile < 2; ++tile) {
-            const v8h vf = tile ? vf1 : vf0;
+        for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16((tb >> 1) ? vf1 : vf0, (tb & 1) ? uf1 : uf0, z, 0, 0, 0);
+    };
+    auto sign_and_add = [&](auto first, int tb, const v16f& m, const SIn& sg) {
+        const int tile = tb >> 1, rg = tb & 1;
+        const unsigned wrd = ~(tile ? sg.w[rg].y : sg.w[rg].x) >> (4 * hl);
 #pragma unroll
-            for (int rg = 0; rg < 2; ++rg) {
+        for (int mf = 0; mf < 2; ++mf) {
+            unsigned r4[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+                h2 c;
+                c[0] = _Float16(m[4 * mf + k]);
+                c[1] = _Float16(m[4 * mf + k + 8]);
+                const unsigned flip = (wrd << (15 - 8 * mf - k)) & 0x80008000u;
+                r4[k] = __builtin_bit_cast(unsigned, c) ^ flip;
+            }
+            if (decltype(first)::value && mf == 0) {
                 v16f z;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) z[v] = 0.0f;
-                const v16f m = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, rg ? uf1 : uf0, z, 0, 0, 0);
-                const unsigned wrd = ~(tile ? sg.w[rg].y : sg.w[rg].x) >> (4 * hl);
-#pragma unroll
-                for (int mf = 0; mf < 2; ++mf) {
-                    unsigned r4[4];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-                        h2 c;
-                        c[0] = _Float16(m[4 * mf + k]);
-                        c[1] = _Float16(m[4 * mf + k + 8]);
-                        const unsigned flip = (wrd << (15 - 8 * mf - k)) & 0x80008000u;
-                        r4[k] = __builtin_bit_cast(unsigned, c) ^ flip;
-                    }
-                    if (decltype(first)::value && mf == 0)
-                        wacc[tile][rg] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ident[mf], __builtin_bit_cast(v8h, r4), z, 0, 0, 0);
-                    else
-                        wacc[tile][rg] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ident[mf], __builtin_bit_cast(v8h, r4),
-                                                                                wacc[tile][rg], 0, 0, 0);
-                }
+                wacc[tile][rg] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ident[mf], __builtin_bit_cast(v8h, r4), z, 0, 0, 0);
+            } else {
+                wacc[tile][rg] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ident[mf], __builtin_bit_cast(v8h, r4),
+                                                                        wacc[tile][rg], 0, 0, 0);
             }
         }
+    };
+    // tile-blocks tb = 2 * tile + row group
+    auto rebuild = [&](auto first, const SIn& sg, v8h uf0, v8h uf1, v8h vf0, v8h vf1) {
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) sign_and_add(first, tb, magnitude(tb, uf0, uf1, vf0, vf1), sg);
     };
 
     // end of a chunk: park my piece of W' diag(1/s) in LDS, then the product stage for both teams' chunks

@@ -131,3 +131,27 @@ def test_staged_block_equals_its_slot_in_the_whole_image():
         assert np.array_equal(st[vm_off: vm_off + inn * 2], img[off_vmax + i * inn * 2: off_vmax + (i + 1) * inn * 2])
     with pytest.raises(B.BitStackError):
         B.stage_block_host(sw[0], U[0], V[0], np.empty(16, dtype=np.uint8))
+
+
+def test_kernel_choice_is_host_logic():
+    """bitstack_choose_kernel: one token always takes the decode kernel; the materialising path is
+    chosen only with a scratch buffer of out x in fp16 values and a stack the restore kernel can
+    hold, and only for prefill-sized batches."""
+    import paper_2410_23918_amd as B
+    big = 1 << 40
+    assert B.choose_kernel(4096, 4096, 16, 1, 1, 16) == B.KERNEL_DECODE
+    assert B.choose_kernel(4096, 4096, 16, 2048, 1, 16, big) == B.KERNEL_DECODE
+    assert B.choose_kernel(28672, 8192, 16, 2048, 2048, 16, big) == B.KERNEL_MATERIALISE
+    assert B.choose_kernel(28672, 8192, 16, 2048, 2048, 16, 0) == B.KERNEL_PANEL
+    assert B.choose_kernel(28672, 8192, 16, 2048, 2048, 16, B.dense_bytes(28672, 8192) - 1) == B.KERNEL_PANEL
+    assert B.choose_kernel(28672, 8192, 16, 2048, 2048, 16, B.dense_bytes(28672, 8192)) == B.KERNEL_MATERIALISE
+    assert B.choose_kernel(28672, 8192, 16, 2048, 128, 16, big) == B.KERNEL_PANEL
+    assert B.choose_kernel(14336, 4096, 32, 2048, 2048, B.restore_max_blocks() + 1, big) == B.KERNEL_PANEL
+    assert B.choose_kernel(14336, 4096, 16, 16, 16, 16, big) == B.KERNEL_PANEL      # too few tokens to pay for restoring
+    assert B.choose_kernel(4096, 4096, 16, 64, 2, 2, big) in (B.KERNEL_DECODE, B.KERNEL_PANEL)
+    assert B.choose_kernel(4096, 4096, 16, 64, 2, 0) == B.KERNEL_AUTO
+    L = B.lib()
+    assert L.bitstack_choose_kernel(4096, 100, 16, 1, 1, 1, 0) == -2
+    assert L.bitstack_choose_kernel(4096, 4096, 16, 8, 9, 1, 0) == -3
+    assert L.bitstack_choose_kernel(4096, 4096, 16, 8, 1, 17, 0) == -3
+    assert B.dense_bytes(4096, 100) == 0

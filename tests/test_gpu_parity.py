@@ -471,12 +471,49 @@ def test_materialised_path_every_tile_variant(B, out, inn, n):
     assert not y.any()
 
 
+def test_library_choice_with_an_optional_scratch_buffer(B):
+    """bitstack_linear_batched_ws: same results with and without the scratch buffer; the buffer is
+    overwritten exactly when the host-side choice says so, left alone otherwise."""
+    import torch
+    out, inn, n, T = 8192, 1024, 4, 2048
+    st = synth_stack(3, out, inn, n)
+    ps = _pack(B, st, max_batch=T)
+    x = acts(3, T, inn)
+    ref = O.forward_dense(st, x, n)
+    ws = torch.full((out, inn), 3.0, dtype=torch.float16, device="cuda:0")
+    for b in (1, 40, 200, 2048):
+        choice = B.choose_kernel(out, inn, n, T, b, n, ws.numel() * 2)
+        ws.fill_(3.0)
+        xd = _to_dev(x[:b])
+        y1 = ps.linear_batched_ws(xd, n, ws)
+        y0 = ps.linear_batched_ws(xd, n, None)
+        torch.cuda.synchronize()
+        touched = bool((ws != 3.0).any())
+        print(f"{out}x{inn} B={b}: choice {choice}, scratch touched: {touched}", flush=True)
+        assert touched == (choice == B.KERNEL_MATERIALISE)
+        for y in (y0, y1):
+            err = O.relative_error(y.float().cpu().numpy(), ref[:b])
+            assert err <= TOL
+    assert B.choose_kernel(out, inn, n, T, 2048, n, ws.numel() * 2) == B.KERNEL_MATERIALISE
+    assert B.choose_kernel(out, inn, n, T, 1, n, ws.numel() * 2) == B.KERNEL_DECODE
+    # too small a buffer is ignored, a misaligned one is an error
+    small = torch.empty(1024, dtype=torch.float16, device="cuda:0")
+    y = ps.linear_batched_ws(_to_dev(x), n, small)
+    torch.cuda.synchronize()
+    assert O.relative_error(y.float().cpu().numpy(), ref) <= TOL
+    L = B.lib()
+    assert L.bitstack_linear_batched_ws(C.c_void_p(y.data_ptr()), 1, ps.handle, n, C.c_void_p(y.data_ptr()), 0,
+                                        C.c_void_p(ws.data_ptr() + 16), ws.numel() * 2, None) == -4
+    assert L.bitstack_linear_select(C.c_void_p(y.data_ptr()), 1, ps.handle, n, C.c_void_p(y.data_ptr()), 0,
+                                    B.KERNEL_MATERIALISE, None) == -8
+
+
 def test_materialised_path_argument_errors(B):
     import torch
     L = B.lib()
     st = synth_stack(3, 64, 512, 30)
     ps = _pack(B, st, max_batch=100)
-    small = _pack(B, st, max_batch=8)          # no activation scratch in this image
+    small = _pack(B, st, max_batch=8)
     x = _to_dev(acts(3, 100, 512))
     y = torch.empty((100, 64), dtype=torch.float16, device="cuda:0")
     wd = torch.empty((64 * 512 + 64,), dtype=torch.float16, device="cuda:0")
@@ -488,7 +525,7 @@ def test_materialised_path_argument_errors(B):
     assert L.bitstack_restore_weight(ps.handle, 2, vp(wd.data_ptr() + 16), nb, None) == -4
     assert L.bitstack_restore_weight(ps.handle, 2, None, nb, None) == -1
     assert L.bitstack_linear_dense(vp(x.data_ptr()), 101, ps.handle, vp(wd.data_ptr()), vp(y.data_ptr()), 0, None) == -3
-    assert L.bitstack_linear_dense(vp(x.data_ptr()), 8, small.handle, vp(wd.data_ptr()), vp(y.data_ptr()), 0, None) == -3
+    assert L.bitstack_linear_dense(vp(x.data_ptr()), 9, small.handle, vp(wd.data_ptr()), vp(y.data_ptr()), 0, None) == -3
     assert L.bitstack_linear_dense(vp(x.data_ptr()), 8, ps.handle, vp(wd.data_ptr()), vp(y.data_ptr()), 5, None) == -8
     assert L.bitstack_linear_materialised(vp(x.data_ptr()), 8, ps.handle, 2, vp(wd.data_ptr()), nb - 2,
                                           vp(y.data_ptr()), 0, None) == -6
