@@ -197,6 +197,12 @@ __device__ __forceinline__ float wave_max(float v) {
 //     LDS.
 // One barrier per block separates "fragments of block q+1 written" from "fragments of
 // block q read".
+// raw V values of GG consecutive 16-value panel groups (one thread's share of a slab)
+template <int GG>
+struct RawT {
+    uint4 v[GG][2];
+};
+
 template <int KS>
 __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KGroup grp) {
     constexpr int NCH = KS / kChunkCols;   // sign chunks per slab
@@ -253,10 +259,95 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
         return a;
     };
 
+    // quantise block q's slab of the panel from raw V into fragment buffer (q & 1): thread ti of a
+    // team of KS / GG threads takes the GG consecutive 16-value groups ti * GG ..: panel position
+    // (ti * GG) / 16 (one 32-column operand of one class) and the ranks rk0 .. rk0 + GG - 1.
+    // The producers use it with 4 groups per thread; block 0 is done by the consumers (twice the
+    // threads, idle until their first signs arrive) from the raw values they fetched at entry.
+    auto quantise = [&](int ti, int q, const auto raw) {
+        constexpr int GG = int(sizeof(raw.v) / sizeof(raw.v[0]));
+        v4i* frag = frag0 + (q & 1) * (FRAG_BYTES / 16);
+        int* csq = cs + (q % 3) * 32;
+        const float amax = amax_of(q);
+        const float inv = amax > 0.0f ? (kQMax / 32767.0f) / amax : 0.0f;
+        const int gbase = ti * GG;             // first group of this thread
+        const int pos = gbase >> 4, rk0 = gbase & 15;
+        const int g = pos & 1, t = (pos >> 1) & 7, c = pos >> 4;
+        // the sign byte of class t is 2^(t%4) (high-nibble classes are shifted down by
+        // the consumers): pre-dividing by it puts every class on one scale,
+        // (sign byte) * q = 32512 * T / amax
+        const int tc = t & 3;
+        const float f = inv * __int_as_float((127 - tc) << 23);   // inv * 2^-tc
+        float xf[16];
+        {
+            const float4* xg = reinterpret_cast<const float4*>(xs + pos * 16);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float4 v = xg[k];
+                xf[4 * k] = v.x * f; xf[4 * k + 1] = v.y * f; xf[4 * k + 2] = v.z * f; xf[4 * k + 3] = v.w * f;
+            }
+        }
+        int sums[GG][2];
+#pragma unroll
+        for (int m = 0; m < GG; ++m) {
+            const uint4 va = raw.v[m][0], vb = raw.v[m][1];
+            const unsigned vw[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
+            unsigned qq[8];
+#pragma unroll
+            for (int e2 = 0; e2 < 8; ++e2) {
+                typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+                const h2v h = __builtin_bit_cast(h2v, vw[e2]);
+                // + 128 (in units of the 16-bit code) rides along in the multiply-add that also converts
+                // the fp16 factor: the high byte of q + 128 is round(q / 256), the low byte q ^ 0x80
+                constexpr float kHalfByte = 128.0f / 32767.0f;
+                const v2s qv = __builtin_amdgcn_cvt_pknorm_i16(__builtin_fmaf(float(h[0]), xf[2 * e2], kHalfByte),
+                                                               __builtin_fmaf(float(h[1]), xf[2 * e2 + 1], kHalfByte));
+                qq[e2] = __builtin_bit_cast(unsigned, qv);
+            }
+            v4i H, L;
+            int sH = 0, sL = 0;
+#pragma unroll
+            for (int w4 = 0; w4 < 4; ++w4) {
+                const unsigned hi = __builtin_amdgcn_perm(qq[2 * w4 + 1], qq[2 * w4], 0x07050301u);
+                const unsigned lo = __builtin_amdgcn_perm(qq[2 * w4 + 1], qq[2 * w4], 0x06040200u) ^ 0x80808080u;
+                H[w4] = int(hi);
+                L[w4] = int(lo);
+                sH = __builtin_amdgcn_sdot4(int(hi), 0x01010101, sH, false);
+                sL = __builtin_amdgcn_sdot4(int(lo), 0x01010101, sL, false);
+            }
+            sums[m][0] = sH << tc;
+            sums[m][1] = sL << tc;
+            const int r = rk0 + m;
+            const int lane_hi = g * 32 + 8 * (r >> 2) + (r & 3);
+            frag[(c * 8 + t) * 64 + lane_hi] = H;
+            frag[(c * 8 + t) * 64 + lane_hi + 4] = L;
+        }
+        // integer column sums of the quantised panel per rank and byte half: add up the
+        // lanes that hold the same ranks (lane bits above log2(16 / GG)), then one LDS
+        // atomic per rank, half and wavefront
+        constexpr int RSTEP = 16 / GG;   // lanes per full set of ranks
+#pragma unroll
+        for (int m = 0; m < GG; ++m)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                int v = sums[m][h];
+#pragma unroll
+                for (int off = RSTEP; off < 64; off <<= 1) v += __shfl_xor(v, off);
+                sums[m][h] = v;
+            }
+        if (lane < RSTEP) {
+#pragma unroll
+            for (int m = 0; m < GG; ++m) {
+                atomicAdd(&csq[rk0 + m], sums[m][0]);
+                atomicAdd(&csq[16 + rk0 + m], sums[m][1]);
+            }
+        }
+    };
+
     BS_TRACE(0);
     // Both roles pass the same barriers: P1 (x/s slab and the first blocks' maxima in LDS), P2
     // (remaining maxima; only if the workgroup has more than kMaxPre blocks), P3 (block 0
-    // staged), then one per block.
+    // staged, by the consumers), then one per block.
     if (producer) {
         // ============================================================== producers
         // one producer wave shares a SIMD with two consumer waves that are almost never
@@ -267,14 +358,10 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
         // Raw V slab and U rows of a block are fetched one stage ahead (always issued, for
         // a block index clamped to the last one, so that the in-order memory counter lets
         // the older set be consumed while the younger one is still in flight).
-        struct Raw {
-            uint4 v[G][2];
-        };
+        using Raw = RawT<G>;
         struct URows {
             uint4 u[PER];
         };
-        // Thread ptid stages G consecutive 16-value groups: panel position (ptid*G)/16
-        // (one 32-column operand of one class) and the ranks rk0 .. rk0+G-1.
         static_assert(G == 4 || G == 2 || G == 1, "group mapping");
         auto load_raw = [&](int q) -> Raw {
             Raw raw;
@@ -307,86 +394,6 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
 #pragma unroll
             for (int k = 0; k < PER; ++k) udst[ptid + k * PT] = ur.u[k];
         };
-        // quantise block q's slab of the panel from raw V into fragment buffer (q & 1)
-        auto quantise = [&](int q, const Raw raw) {
-            v4i* frag = frag0 + (q & 1) * (FRAG_BYTES / 16);
-            int* csq = cs + (q % 3) * 32;
-            const float amax = amax_of(q);
-            const float inv = amax > 0.0f ? (kQMax / 32767.0f) / amax : 0.0f;
-            const int gbase = ptid * G;            // first group of this thread
-            const int pos = gbase >> 4, rk0 = gbase & 15;
-            const int g = pos & 1, t = (pos >> 1) & 7, c = pos >> 4;
-            // the sign byte of class t is 2^(t%4) (high-nibble classes are shifted down by
-            // the consumers): pre-dividing by it puts every class on one scale,
-            // (sign byte) * q = 32512 * T / amax
-            const int tc = t & 3;
-            const float f = inv * __int_as_float((127 - tc) << 23);   // inv * 2^-tc
-            float xf[16];
-            {
-                const float4* xg = reinterpret_cast<const float4*>(xs + pos * 16);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const float4 v = xg[k];
-                    xf[4 * k] = v.x * f; xf[4 * k + 1] = v.y * f; xf[4 * k + 2] = v.z * f; xf[4 * k + 3] = v.w * f;
-                }
-            }
-            int sums[G][2];
-#pragma unroll
-            for (int m = 0; m < G; ++m) {
-                const uint4 va = raw.v[m][0], vb = raw.v[m][1];
-                const unsigned vw[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
-                unsigned qq[8];
-#pragma unroll
-                for (int e2 = 0; e2 < 8; ++e2) {
-                    typedef _Float16 h2v __attribute__((ext_vector_type(2)));
-                    const h2v h = __builtin_bit_cast(h2v, vw[e2]);
-                    // + 128 (in units of the 16-bit code) rides along in the multiply-add that also converts
-                    // the fp16 factor: the high byte of q + 128 is round(q / 256), the low byte q ^ 0x80
-                    constexpr float kHalfByte = 128.0f / 32767.0f;
-                    const v2s qv = __builtin_amdgcn_cvt_pknorm_i16(__builtin_fmaf(float(h[0]), xf[2 * e2], kHalfByte),
-                                                                   __builtin_fmaf(float(h[1]), xf[2 * e2 + 1], kHalfByte));
-                    qq[e2] = __builtin_bit_cast(unsigned, qv);
-                }
-                v4i H, L;
-                int sH = 0, sL = 0;
-#pragma unroll
-                for (int w4 = 0; w4 < 4; ++w4) {
-                    const unsigned hi = __builtin_amdgcn_perm(qq[2 * w4 + 1], qq[2 * w4], 0x07050301u);
-                    const unsigned lo = __builtin_amdgcn_perm(qq[2 * w4 + 1], qq[2 * w4], 0x06040200u) ^ 0x80808080u;
-                    H[w4] = int(hi);
-                    L[w4] = int(lo);
-                    sH = __builtin_amdgcn_sdot4(int(hi), 0x01010101, sH, false);
-                    sL = __builtin_amdgcn_sdot4(int(lo), 0x01010101, sL, false);
-                }
-                sums[m][0] = sH << tc;
-                sums[m][1] = sL << tc;
-                const int r = rk0 + m;
-                const int lane_hi = g * 32 + 8 * (r >> 2) + (r & 3);
-                frag[(c * 8 + t) * 64 + lane_hi] = H;
-                frag[(c * 8 + t) * 64 + lane_hi + 4] = L;
-            }
-            // integer column sums of the quantised panel per rank and byte half: add up the
-            // lanes that hold the same ranks (lane bits above log2(16 / G)), then one LDS
-            // atomic per rank, half and wavefront
-            constexpr int RSTEP = 16 / G;   // lanes per full set of ranks
-#pragma unroll
-            for (int m = 0; m < G; ++m)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    int v = sums[m][h];
-#pragma unroll
-                    for (int off = RSTEP; off < 64; off <<= 1) v += __shfl_xor(v, off);
-                    sums[m][h] = v;
-                }
-            if (lane < RSTEP) {
-#pragma unroll
-                for (int m = 0; m < G; ++m) {
-                    atomicAdd(&csq[rk0 + m], sums[m][0]);
-                    atomicAdd(&csq[16 + rk0 + m], sums[m][1]);
-                }
-            }
-        };
-
         // ---- activation slab x/s in panel order (once per workgroup); the per-channel
         // maxima of my first blocks and block 0's raw data are requested at the same time
         if (ptid < 96) cs[ptid] = 0;
@@ -410,8 +417,6 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
                                ptid * XP;
             hv[k] = *reinterpret_cast<const HVec*>(vm);
         }
-        Raw ra = load_raw(0);
-        const URows u0 = load_u(0);
         // ---- exact max |V[j][r] * xs[j]| over the slab for each of my blocks:
         //      max_j |xs[j]| * max_r |V[j][r]|, the inner maximum stored at pack time.
         //      The first NPRE blocks are done from registers before the first barrier.
@@ -453,13 +458,10 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
             lds_barrier();   // P2
         }
         BS_TRACE(2);
+        Raw ra;
         Raw rb = load_raw(1);
         BS_TRACE2(1, 19);
-        quantise(0, ra);
-        BS_TRACE2(1, 20);
-        store_u(0, u0);
-        BS_TRACE2(1, 21);
-        lds_barrier();   // P3
+        lds_barrier();   // P3 (block 0 is staged by the consumers)
         BS_TRACE2(1, 22);
         BS_TRACE(3);
         // interval q: stage block q + 1 (raw V already here), fetch block q + 2's raw V
@@ -468,7 +470,7 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
             if (ptid < 32) cs[((q + 2) % 3) * 32 + ptid] = 0;   // last read two barriers ago
             ra = load_raw(q + 2);
             if (q + 1 < nb) {
-                quantise(q + 1, rb);
+                quantise(ptid, q + 1, rb);
                 store_u(q + 1, load_u(q + 1));   // producers have slack: latency exposed here is free
             }
             BS_TRACE2(1, 2 * q + 1);
@@ -478,7 +480,7 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
                 if (ptid < 32) cs[((q + 3) % 3) * 32 + ptid] = 0;
                 rb = load_raw(q + 3);
                 if (q + 2 < nb) {
-                    quantise(q + 2, ra);
+                    quantise(ptid, q + 2, ra);
                     store_u(q + 2, load_u(q + 2));
                 }
                 BS_TRACE2(1, 2 * q + 3);
@@ -583,20 +585,60 @@ __global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KG
             }
         };
 
-        lds_barrier();   // P1
-        BS_TRACE(1);
-        // The sign stream starts only now.  Requested at kernel entry it would not arrive sooner:
-        // a wavefront cannot even issue its 16 KiB window faster than the memory system, asked by
-        // every compute unit at once, takes requests (the issue alone lasts ~2.4 us), so it would
-        // only reach this barrier later and hold up the producers' prologue.
+        // Block 0 is staged by the consumers: they have twice the producers' threads, two
+        // wavefronts per SIMD, and nothing else to do until their first signs arrive (0.7 us
+        // against 3.5 us in the producers).  Its raw V values and U rows are requested first, then
+        // the whole sign window of block 0 (loads return in order: what is needed first is asked
+        // for first).  Issuing the window takes until ~6 us after entry when every compute unit
+        // asks at once (requests are accepted at the rate data returns); asking for half of it
+        // here and the rest at the start of block 0, or for all of it after the barriers,
+        // measured 2-5 % slower.
+        constexpr int CT = kConsumers * 64;
+        constexpr int CG = KS >= CT ? KS / CT : 1;   // 16-value groups per consumer thread
+        constexpr int CACT = KS / CG;                // consumer threads that quantise
+        constexpr int UPER = U_BYTES / 16 / CT;
+        static_assert(UPER == 4, "four named registers below (an array of load results ends up in scratch memory)");
+        RawT<CG> r0;
+        uint4 u00, u01, u02, u03;
+        {
+            const unsigned char* blk = block_ptr(0);
+            const uint4* vsl = reinterpret_cast<const uint4*>(blk + p.off_v) + size_t(c0) * 256 * 2 +
+                               size_t(min(tid, CACT - 1)) * CG * 2;
+#pragma unroll
+            for (int m = 0; m < CG; ++m) {
+                r0.v[m][0] = vsl[m * 2];
+                r0.v[m][1] = vsl[m * 2 + 1];
+            }
+            const uint4* usrc = reinterpret_cast<const uint4*>(blk + p.off_u);
+            const int last_piece = p.out * 2 - 1;   // rows past the end: re-read the last valid piece
+            u00 = usrc[min(row0 * 2 + tid, last_piece)];
+            u01 = usrc[min(row0 * 2 + tid + CT, last_piece)];
+            u02 = usrc[min(row0 * 2 + tid + 2 * CT, last_piece)];
+            u03 = usrc[min(row0 * 2 + tid + 3 * CT, last_piece)];
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
 #pragma unroll
             for (int tl = 0; tl < R; ++tl)
                 win[c][tl] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, unit_off(0, tl) + c * kUnitBytes, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        BS_TRACE2(0, 16);
+        ulds[tid] = u00;
+        ulds[tid + CT] = u01;
+        ulds[tid + 2 * CT] = u02;
+        ulds[tid + 3 * CT] = u03;
+        BS_TRACE2(0, 17);
+        lds_barrier();   // P1
+        BS_TRACE2(0, 18);
+        BS_TRACE(1);
         if (nb > kMaxPre) lds_barrier();   // P2
         BS_TRACE(2);
+        BS_TRACE2(0, 19);
+        if (tid < CACT) quantise(tid, 0, r0);
+        BS_TRACE2(0, 20);
         lds_barrier();   // P3
+        BS_TRACE2(0, 21);
         BS_TRACE(3);
         for (int q = 0; q < nb; ++q) {
             BS_TRACE2(0, 2 * q);
