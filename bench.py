@@ -172,6 +172,34 @@ def batch_table(B, torch, dev, n):
     return rows
 
 
+def decompose_table(B, torch, dev, iterations=20):
+    """The decomposition on the device (bitstack_decompose): time per residual block at the 4096x4096
+    and 14336x4096 shapes.  Algorithmic bytes per block: the fp32 residual is read once by each of
+    the 2 * iterations + 2 tall products and by the sign packing, and read and written once by the
+    residual update."""
+    from workloads import synth as W
+    rows = []
+    for cfg, (o, i), nblk in ((2, (4096, 4096), 4), (3, (14336, 4096), 2)):
+        c = W.CONFIGS[cfg]
+        rng = W.rng_for(cfg, 0)
+        Wt = W.dense_weight(rng, o, i, c["sigma_w"], c["fp16_weights"])
+        s = W.column_scales(rng, i)
+        Wd = torch.from_numpy(np.ascontiguousarray(Wt, dtype=np.float32)).to(dev)
+        B.decompose(Wd, s, 1, iterations=iterations)          # warm-up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        sw, U, V = B.decompose(Wd, s, nblk, iterations=iterations)   # synchronises before returning
+        ms = (time.perf_counter() - t0) * 1e3 / nblk
+        bytes_per_block = (2 * iterations + 2 + 1 + 2) * o * i * 4
+        gbs = bytes_per_block / ms / 1e6
+        log(f"[bench] decomposition on the device {o}x{i}, {iterations} iterations: {ms:.1f} ms per block, "
+            f"{gbs:.0f} GB/s of residual traffic ({gbs / HBM_PEAK_GBS * 100:.1f}% of 8 TB/s)")
+        rows.append({"shape": f"{o}x{i}", "iterations": iterations, "ms_per_block": round(ms, 2),
+                     "residual_GBs": round(gbs, 1)})
+        del Wd, sw, U, V
+    return rows
+
+
 def decoder_token(B, torch, dev, layers=32, n_pack=24):
     """Config 4: one token through 7 linears x 32 layers, per-matrix n_loaded ~ U{8..24}.
     One layer's seven stacks are generated on the host; every layer gets its own packed
@@ -259,6 +287,8 @@ def main():
     ap.add_argument("--decoder", action="store_true",
                     help="also time one token through all 224 linears of a Llama-3-8B-shaped decoder with "
                          "per-matrix n_loaded ~ U{8..24} (config 4; needs ~25 GB of HBM, takes a minute to pack)")
+    ap.add_argument("--decompose", action="store_true",
+                    help="also time the decomposition on the device (4096x4096 and 14336x4096)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--headline-only", action="store_true",
                     help="skip the side measurements (same-buffer and merged-launch variants), so that a profiler "
@@ -352,6 +382,8 @@ def main():
         extra["batch_path"] = batch_table(B, torch, dev, n)
     if args.decoder:
         extra["decoder_token"] = decoder_token(B, torch, dev)
+    if args.decompose:
+        extra["decomposition"] = decompose_table(B, torch, dev)
 
     result = {
         "metric": "effective block-stream GB/s, batch-1 decode, n=16 k=16, Llama-3-8B 4096x4096 projection",

@@ -240,6 +240,30 @@ int bitstack_linear_materialised(const void* x, int batch, const bitstack_weight
                                  int n_loaded, void* w_dense, size_t w_dense_bytes, void* y,
                                  int y_dtype, bitstack_stream_t stream);
 
+/* The decomposition itself on the device (Section 2.1: activation-aware scaling, Eq. 3-4, and
+ * the iterative absolute value decomposition, Eq. 5-7):
+ *     R_0 = W diag(s);   per block i:  S_i = sign(R_i) (sign(0) = +1),
+ *     U_i V_i^T = the top-k singular triplets of |R_i| with sqrt(sigma) on either side (Eq. 2),
+ *     rounded to fp16;   R_{i+1} = R_i - S_i (.) (U_i V_i^T)  with the factors as stored.
+ * The singular triplets come from a block power (subspace) iteration with k + 16 columns and
+ * `iterations` rounds (0 = 20; one round applies |R| |R|^T once) followed by a Rayleigh-Ritz step, in fp32 (small Gram and
+ * eigenvalue problems in fp64).
+ *   W: device fp32 [out][in] row-major, 16-byte aligned (not modified).
+ *   s: HOST fp32 [in], every entry finite and > 0 (BITSTACK_E_SCALE otherwise); copied by the call.
+ *   sign_words: device uint32 [n][out][in/32], canonical layout (bit b of word w = column 32w+b,
+ *   1 = +1);  U: device fp16 bits [n][out][k];  V: device fp16 bits [n][in][k] -- the inputs of
+ *   bitstack_pack_blocks once copied to the host.
+ *   workspace: device, caller-owned, 256-byte aligned, at least
+ *   bitstack_decompose_workspace_bytes(out, in, k) bytes (BITSTACK_E_BUFSIZE otherwise); it holds
+ *   the fp32 residual (out x in x 4 bytes) and the iteration's tall matrices.
+ * Asynchronous (the copy of s aside), allocates nothing.  The factors of a block are unique only
+ * up to the sign of each column pair and rotations inside clusters of equal singular values;
+ * U_i V_i^T and the residual norms are what can be compared between implementations. */
+size_t bitstack_decompose_workspace_bytes(int out, int in, int k);
+int bitstack_decompose(const float* W, const float* s, int out, int in, int k, int n, int iterations,
+                       uint32_t* sign_words, uint16_t* U, uint16_t* V, void* workspace,
+                       size_t workspace_bytes, bitstack_stream_t stream);
+
 /* Tuning hooks for benchmarks (process-wide, not thread-safe).  value 0 restores
  * the built-in choice.  Unknown options or unsupported values give BITSTACK_E_ARG
  * (at the next launch for values). */

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     block_bytes,
     block_staging_bytes,
     dense_bytes,
+    decompose,
     choose_kernel,
     restore_max_blocks,
     stage_block_host,

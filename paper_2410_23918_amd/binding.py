@@ -85,6 +85,10 @@ def lib():
     L.bitstack_linear_batched_ws.restype = i32
     L.bitstack_choose_kernel.argtypes = [i32, i32, i32, i32, i32, i32, sz]
     L.bitstack_choose_kernel.restype = i32
+    L.bitstack_decompose_workspace_bytes.restype = sz
+    L.bitstack_decompose_workspace_bytes.argtypes = [i32, i32, i32]
+    L.bitstack_decompose.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+    L.bitstack_decompose.restype = i32
     L.bitstack_release.argtypes = [vp]
     L.bitstack_release.restype = None
     L.bitstack_strerror.restype = C.c_char_p
@@ -193,6 +197,29 @@ def choose_kernel(out: int, inn: int, n_slots: int, max_batch: int, batch: int, 
     if rc < 0:
         raise BitStackError(rc, "bitstack_choose_kernel")
     return rc
+
+
+def decompose(W, s, n: int, k: int = 16, iterations: int = 0, stream=None):
+    """bitstack_decompose: W is a device fp32 tensor [out][in], s a host array [in].  Returns device
+    tensors (sign_words int32 [n][out][in/32], U fp16 [n][out][k], V fp16 [n][in][k])."""
+    import torch
+    out, inn = W.shape
+    s = np.ascontiguousarray(s, dtype=np.float32)
+    dev = W.device
+    sw = torch.empty((n, out, inn // 32), dtype=torch.int32, device=dev)
+    U = torch.empty((n, out, k), dtype=torch.float16, device=dev)
+    V = torch.empty((n, inn, k), dtype=torch.float16, device=dev)
+    nbytes = int(lib().bitstack_decompose_workspace_bytes(out, inn, k))
+    if nbytes == 0:
+        raise BitStackError(-2, "bitstack_decompose_workspace_bytes")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    if stream is None:
+        stream = torch.cuda.current_stream(dev)
+    _check(lib().bitstack_decompose(W.data_ptr(), _ptr(s), out, inn, k, n, iterations, sw.data_ptr(), U.data_ptr(),
+                                    V.data_ptr(), ws.data_ptr(), nbytes, C.c_void_p(stream.cuda_stream)),
+           "bitstack_decompose")
+    stream.synchronize()   # the workspace is released when this function returns
+    return sw, U, V
 
 
 def restore_max_blocks() -> int:

@@ -468,6 +468,35 @@ int bitstack_linear_materialised(const void* x, int batch, const bitstack_weight
     return bitstack_linear_dense(x, batch, w, w_dense, y, y_dtype, stream);
 }
 
+size_t bitstack_decompose_workspace_bytes(int out, int in, int k) {
+    if (!shape_ok(out, in, k)) return 0;
+    return align256(size_t(in) * 4) + decompose_workspace_bytes(out, in, decompose_slices(out, in));
+}
+
+int bitstack_decompose(const float* W, const float* s, int out, int in, int k, int n, int iterations,
+                       uint32_t* sign_words, uint16_t* U, uint16_t* V, void* workspace, size_t workspace_bytes,
+                       bitstack_stream_t stream) {
+    if (!W || !s || !sign_words || !U || !V || !workspace) return BITSTACK_E_NULL;
+    if (!shape_ok(out, in, k)) return BITSTACK_E_SHAPE;
+    if (n < 0 || iterations < 0 || iterations > 1000) return BITSTACK_E_RANGE;
+    for (int j = 0; j < in; ++j)
+        if (!std::isfinite(s[j]) || !(s[j] > 0.0f)) return BITSTACK_E_SCALE;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 || reinterpret_cast<uintptr_t>(W) % 16 ||
+        reinterpret_cast<uintptr_t>(sign_words) % 4 || reinterpret_cast<uintptr_t>(U) % 2 ||
+        reinterpret_cast<uintptr_t>(V) % 2)
+        return BITSTACK_E_ALIGN;
+    if (workspace_bytes < bitstack_decompose_workspace_bytes(out, in, k)) return BITSTACK_E_BUFSIZE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    BS_HIP(hipMemcpyAsync(ws, s, size_t(in) * 4, hipMemcpyHostToDevice, st));
+    if (n == 0) return BITSTACK_OK;
+    hipError_t e = launch_decompose(W, reinterpret_cast<const float*>(ws), out, in, n, iterations ? iterations : 20, sign_words,
+                                    reinterpret_cast<__half*>(U), reinterpret_cast<__half*>(V),
+                                    ws + align256(size_t(in) * 4), st);
+    if (e != hipSuccess) return hip_fail(e);
+    return BITSTACK_OK;
+}
+
 int bitstack_probe_read(const void* device_buf, size_t bytes, void* device_sink, int workgroups,
                         bitstack_stream_t stream) {
     if (!device_buf || !device_sink) return BITSTACK_E_NULL;

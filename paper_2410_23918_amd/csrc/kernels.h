@@ -1,6 +1,8 @@
 // Internal interface between the C-ABI host code and the HIP kernels.
 #pragma once
+#include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
+#include <stdint.h>
 
 #include "layout.h"
 
@@ -36,6 +38,12 @@ hipError_t launch_restore(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_dense_zero(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_dense(const LaunchArgs& a, hipStream_t st);
 int restore_max_blocks();
+// decomposition on the device (decompose.hip): W fp32 [out][in], s fp32 [in] (device copy inside the
+// workspace), outputs canonical sign words and fp16 factors on the device
+size_t decompose_workspace_bytes(int out, int in, int slices);
+int decompose_slices(int out, int in);
+hipError_t launch_decompose(const float* W, const float* s, int out, int in, int n, int iters, uint32_t* sign_words,
+                            __half* U, __half* V, unsigned char* workspace, hipStream_t st);
 // column split the small-batch kernel uses for this shape (1 = none)
 int small_batch_split(int out, int in, int batch, int part_slots);
 

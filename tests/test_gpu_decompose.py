@@ -1,0 +1,171 @@
+"""The decomposition on the device (bitstack_decompose) against the CPU oracle's IAVD on the same
+seeded weights.  Singular vectors are not unique (column signs, rotations inside clusters of
+nearly equal singular values: sigma_2 .. sigma_17 of |R| lie within a few per cent of each other),
+so what is compared is what is: the sign matrix of block 0 bit for bit, the residual norms after
+every block, the leading singular value, the validity of every later sign matrix against the
+device's own residual, and the forward pass through the resulting stack."""
+import numpy as np
+import pytest
+
+from oracle import bitstack_oracle as O
+from workloads import synth as W
+
+from _cases import acts, true_stack
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2410_23918_amd as B
+    B.lib()
+    return B
+
+
+def _weights(config, out, inn):
+    cfg = W.CONFIGS[config]
+    rng = W.rng_for(config, 0)
+    Wt = W.dense_weight(rng, out, inn, cfg["sigma_w"], cfg["fp16_weights"])
+    s = W.column_scales(rng, inn)
+    return Wt, s
+
+
+def _residual_norms(Wt, s, S, U, V):
+    """||R_0||_F and ||R_i||_F after every block, in fp64, from the blocks alone."""
+    R = np.asarray(Wt, dtype=np.float64) * np.asarray(s, dtype=np.float64)[None, :]
+    norms = [np.linalg.norm(R)]
+    for i in range(S.shape[0]):
+        R = R - O.block_dense(S[i], U[i], V[i])
+        norms.append(np.linalg.norm(R))
+    return np.array(norms)
+
+
+@pytest.mark.parametrize("config,out,inn,n", [(1, 512, 512, 4), (1, 1056, 768, 3), (1, 96, 2048, 2)])
+def test_device_decomposition_matches_the_oracles(B, config, out, inn, n):
+    import torch
+    Wt, s = _weights(config, out, inn)
+    ref = O.iavd(Wt, s, n, 16)                                 # full LAPACK SVD per block, fp64
+    Wd = torch.from_numpy(np.ascontiguousarray(Wt, dtype=np.float32)).to("cuda:0")
+    sw, U, V = B.decompose(Wd, s, n)
+    torch.cuda.synchronize()
+    sw = sw.cpu().numpy().view(np.uint32)
+    U = U.cpu().numpy()
+    V = V.cpu().numpy()
+    S = np.stack([O.unpack_signs(sw[i], inn) for i in range(n)])
+    assert np.isfinite(U.astype(np.float64)).all() and np.isfinite(V.astype(np.float64)).all()
+
+    # block 0: the sign of W diag(s) does not depend on the arithmetic
+    assert np.array_equal(sw[0], O.pack_signs(ref.S[0]))
+    # every later sign matrix is the sign of the residual the device's own earlier blocks leave
+    # (fp64 replay; entries whose replayed residual is within fp32 rounding of zero may differ)
+    R = np.asarray(Wt, dtype=np.float64) * np.asarray(s, dtype=np.float64)[None, :]
+    scale = np.abs(R).max()
+    for i in range(n):
+        want = O.sign_pm1(R)
+        clear = np.abs(R) > 1e-5 * scale
+        assert np.array_equal(S[i][clear], want[clear]), f"block {i}"
+        assert (~clear).mean() < 1e-3
+        R = R - O.block_dense(S[i], U[i], V[i])
+
+    # residual norms after every block: the truncation error of a rank-16 approximation is
+    # unique (Eckart-Young) even where the vectors are not
+    got = _residual_norms(Wt, s, S, U, V)
+    want = _residual_norms(Wt, s, ref.S, ref.U, ref.V)
+    rel = got[1:] / want[1:] - 1.0
+    print(f"{out}x{inn}: residual norms device/oracle - 1 per block: {np.array2string(rel, precision=5)}", flush=True)
+    assert np.all(rel < 2e-3) and np.all(rel > -2e-3)
+    assert np.all(np.diff(got) < 0)                            # strictly decreasing (BASELINE invariant)
+
+    # the leading singular value of |R_0| through the factors: ||u_0|| ||v_0|| = sigma_0
+    sig0 = np.linalg.svd(np.abs(np.asarray(Wt, dtype=np.float64) * s[None, :]), compute_uv=False)[0]
+    mine = np.linalg.norm(U[0][:, 0].astype(np.float64)) * np.linalg.norm(V[0][:, 0].astype(np.float64))
+    assert abs(mine / sig0 - 1.0) < 2e-3
+    # Eq. 2's split: both factors carry sqrt(sigma)
+    nu, nv = np.linalg.norm(U[0].astype(np.float64), axis=0), np.linalg.norm(V[0].astype(np.float64), axis=0)
+    assert np.allclose(nu, nv, rtol=5e-3)
+
+    # the device's blocks through the device's forward pass against the dense definition
+    st = O.Stack(S, U, V, s)
+    ps = B.PackedStack(sw, U, V, s)
+    x = acts(config, 1, inn)
+    y = ps.linear(torch.from_numpy(x[0]).to("cuda:0"), n)
+    torch.cuda.synchronize()
+    err = O.relative_error(y.float().cpu().numpy()[None], O.forward_dense(st, x, n))
+    assert err <= 2e-3
+    # and it approximates W x as well as the oracle's stack does
+    exact = (x.astype(np.float64) @ np.asarray(Wt, dtype=np.float64).T)
+    e_dev = np.linalg.norm(O.forward_dense(st, x, n) - exact) / np.linalg.norm(exact)
+    e_ref = np.linalg.norm(O.forward_dense(ref, x, n) - exact) / np.linalg.norm(exact)
+    print(f"{out}x{inn}: ||y - Wx|| / ||Wx||: device blocks {e_dev:.4f}, oracle blocks {e_ref:.4f}", flush=True)
+    assert e_dev < 1.1 * e_ref + 1e-3
+
+
+def test_cfg2_device_decomposition_against_full_svd_oracle(B):
+    """Config 2 (4096x4096, n = 16): the oracle's decomposition is the one with a full LAPACK SVD
+    per block that the decode parity test uses as well (cached); residual norms after every one
+    of the 16 blocks, and the decode kernel on the device's own blocks."""
+    import torch
+    out = inn = 4096
+    n = 16
+    Wt, s = _weights(2, out, inn)
+    ref = true_stack(2, out, inn, n)
+    Wd = torch.from_numpy(np.ascontiguousarray(Wt, dtype=np.float32)).to("cuda:0")
+    sw, U, V = B.decompose(Wd, s, n)
+    torch.cuda.synchronize()
+    sw = sw.cpu().numpy().view(np.uint32)
+    U = U.cpu().numpy()
+    V = V.cpu().numpy()
+    assert np.array_equal(sw[0], O.pack_signs(ref.S[0]))
+    S = np.stack([O.unpack_signs(sw[i], inn) for i in range(n)])
+    got = _residual_norms(Wt, s, S, U, V)
+    want = _residual_norms(Wt, s, ref.S, ref.U, ref.V)
+    rel = got[1:] / want[1:] - 1.0
+    print(f"cfg2: residual norms device/oracle - 1, blocks 1..16: {np.array2string(rel, precision=2)}", flush=True)
+    print(f"cfg2: ||R_i|| / ||R_0|| on the device: {np.array2string(got[1:] / got[0], precision=4)}", flush=True)
+    assert np.all(np.abs(rel) < 2e-3)
+    assert np.all(np.diff(got) < 0)
+    st = O.Stack(S, U, V, s)
+    ps = B.PackedStack(sw, U, V, s)
+    x = acts(2, 1, inn)
+    y = ps.linear(torch.from_numpy(x[0]).to("cuda:0"), n)
+    torch.cuda.synchronize()
+    err = O.relative_error(y.float().cpu().numpy()[None], O.forward_dense(st, x, n))
+    print(f"cfg2: decode kernel on the device's blocks: rel err {err:.2e}", flush=True)
+    assert err <= 2e-3
+
+
+def test_decompose_argument_errors(B):
+    import ctypes as C
+    import torch
+    L = B.lib()
+    out, inn = 64, 256
+    Wd = torch.zeros((out, inn), dtype=torch.float32, device="cuda:0")
+    s = np.ones(inn, dtype=np.float32)
+    nb = B.lib().bitstack_decompose_workspace_bytes(out, inn, 16)
+    assert nb > out * inn * 4
+    assert B.lib().bitstack_decompose_workspace_bytes(out, 100, 16) == 0
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+    sw = torch.empty((1, out, inn // 32), dtype=torch.int32, device="cuda:0")
+    U = torch.empty((1, out, 16), dtype=torch.float16, device="cuda:0")
+    V = torch.empty((1, inn, 16), dtype=torch.float16, device="cuda:0")
+    vp = C.c_void_p
+    sp = s.ctypes.data_as(vp)
+    args = lambda **kw: (vp(kw.get("W", Wd.data_ptr())), kw.get("s", sp), kw.get("out", out), kw.get("inn", inn), 16,
+                         kw.get("n", 1), kw.get("it", 2), vp(sw.data_ptr()), vp(U.data_ptr()), vp(V.data_ptr()),
+                         vp(kw.get("ws", ws.data_ptr())), kw.get("nb", nb), None)
+    assert L.bitstack_decompose(*args(W=None)) == -1
+    assert L.bitstack_decompose(*args(inn=100)) == -2
+    assert L.bitstack_decompose(*args(n=-1)) == -3
+    assert L.bitstack_decompose(*args(nb=nb - 1)) == -6
+    assert L.bitstack_decompose(*args(ws=ws.data_ptr() + 16)) == -4
+    bad = s.copy()
+    bad[7] = 0.0
+    assert L.bitstack_decompose(*args(s=bad.ctypes.data_as(vp))) == -5
+    # an all-zero weight: every sign +1, factors zero, nothing non-finite
+    assert L.bitstack_decompose(*args()) == 0
+    torch.cuda.synchronize()
+    assert (sw.cpu().numpy().view(np.uint32) == 0xFFFFFFFF).all()
+    assert torch.isfinite(U.float()).all() and torch.isfinite(V.float()).all()
+    assert not U.any() and not V.any()
