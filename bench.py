@@ -431,8 +431,8 @@ def main():
 
 # HBM bytes per launch of the decode kernel on this workload from rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); see
-# profiles/decode_4096x4096_n16_pmc.txt (39.55 MB fetched + 1.07 MB written; algorithmic 37.75 MB).
-TRAFFIC_BYTES_PER_LAUNCH = 40613090
+# profiles/decode_4096x4096_n16_pmc.txt (40.38 MB fetched + 1.07 MB written; algorithmic 37.75 MB).
+TRAFFIC_BYTES_PER_LAUNCH = 41443857
 
 if __name__ == "__main__":
     main()
