@@ -249,14 +249,15 @@ int bitstack_linear_materialised(const void* x, int batch, const bitstack_weight
  * `iterations` rounds (0 = 20; one round applies |R| |R|^T once) followed by a Rayleigh-Ritz step, in fp32 (small Gram and
  * eigenvalue problems in fp64).
  *   W: device fp32 [out][in] row-major, 16-byte aligned (not modified).
- *   s: HOST fp32 [in], every entry finite and > 0 (BITSTACK_E_SCALE otherwise); copied by the call.
+ *   s: HOST fp32 [in], every entry finite and > 0 (BITSTACK_E_SCALE otherwise); copied to the
+ *   device by a copy enqueued on stream: keep it valid and unchanged until the stream has passed it.
  *   sign_words: device uint32 [n][out][in/32], canonical layout (bit b of word w = column 32w+b,
  *   1 = +1);  U: device fp16 bits [n][out][k];  V: device fp16 bits [n][in][k] -- the inputs of
  *   bitstack_pack_blocks once copied to the host.
  *   workspace: device, caller-owned, 256-byte aligned, at least
  *   bitstack_decompose_workspace_bytes(out, in, k) bytes (BITSTACK_E_BUFSIZE otherwise); it holds
  *   the fp32 residual (out x in x 4 bytes) and the iteration's tall matrices.
- * Asynchronous (the copy of s aside), allocates nothing.  The factors of a block are unique only
+ * Asynchronous, allocates nothing.  The factors of a block are unique only
  * up to the sign of each column pair and rotations inside clusters of equal singular values;
  * U_i V_i^T and the residual norms are what can be compared between implementations. */
 size_t bitstack_decompose_workspace_bytes(int out, int in, int k);
