@@ -155,3 +155,44 @@ def test_kernel_choice_is_host_logic():
     assert L.bitstack_choose_kernel(4096, 4096, 16, 8, 9, 1, 0) == -3
     assert L.bitstack_choose_kernel(4096, 4096, 16, 8, 1, 17, 0) == -3
     assert B.dense_bytes(4096, 100) == 0
+
+
+def test_decompose_and_dense_entry_points_check_arguments_before_touching_the_device():
+    """Every argument error of bitstack_decompose, bitstack_restore_weight and bitstack_linear_dense
+    that does not need a handle is reported before any HIP call (no GPU here)."""
+    import ctypes as C
+    import paper_2410_23918_amd as B
+    L = B.lib()
+    vp = C.c_void_p
+    out, inn = 64, 256
+    nb = L.bitstack_decompose_workspace_bytes(out, inn, 16)
+    assert nb >= out * inn * 4 + (out + inn) * 32 * 4 * 2
+    assert L.bitstack_decompose_workspace_bytes(out, inn, 8) == 0
+    assert L.bitstack_decompose_workspace_bytes(out, 100, 16) == 0
+    assert L.bitstack_decompose_workspace_bytes(4096, 4096, 16) > L.bitstack_decompose_workspace_bytes(2048, 4096, 16)
+    s = np.ones(inn, dtype=np.float32)
+    sp = s.ctypes.data_as(vp)
+    fake = vp(0x10000000)          # never dereferenced: every call below fails before any device work
+    call = lambda **kw: L.bitstack_decompose(kw.get("W", fake), kw.get("s", sp), kw.get("out", out), kw.get("inn", inn),
+                                             kw.get("k", 16), kw.get("n", 1), kw.get("it", 0), fake, fake, fake,
+                                             kw.get("ws", fake), kw.get("nb", nb), None)
+    assert call(W=None) == -1
+    assert call(s=None) == -1
+    assert call(ws=None) == -1
+    assert call(k=8) == -2
+    assert call(inn=100) == -2
+    assert call(n=-1) == -3
+    assert call(it=-1) == -3
+    assert call(it=1001) == -3
+    bad = s.copy()
+    bad[3] = np.inf
+    assert call(s=bad.ctypes.data_as(vp)) == -5
+    bad[3] = -1.0
+    assert call(s=bad.ctypes.data_as(vp)) == -5
+    assert call(ws=vp(0x10000010)) == -4
+    assert call(W=vp(0x10000004)) == -4
+    assert call(nb=nb - 1) == -6
+    assert L.bitstack_restore_weight(None, 1, fake, 1 << 30, None) == -1
+    assert L.bitstack_linear_dense(fake, 1, None, fake, fake, 0, None) == -1
+    assert L.bitstack_linear_dense(None, 1, None, fake, fake, 0, None) == -1
+    assert B.restore_max_blocks() == 29
