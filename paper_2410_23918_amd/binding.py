@@ -65,6 +65,8 @@ def lib():
     L.bitstack_create_stack.restype = i32
     L.bitstack_push_block.argtypes = [vp, vp, vp]
     L.bitstack_push_block.restype = i32
+    L.bitstack_push_block_device.argtypes = [vp, vp, vp, vp, vp]
+    L.bitstack_push_block_device.restype = i32
     L.bitstack_pop_block.argtypes = [vp]
     L.bitstack_pop_block.restype = i32
     L.bitstack_resident_blocks.argtypes = [vp]
@@ -293,6 +295,19 @@ class PackedStack:
                                            self._stream(stream), C.byref(self._h)), "bitstack_create_stack")
         return self
 
+    @classmethod
+    def from_dense(cls, W, s, n: int, k: int = 16, iterations: int = 0, max_batch: int = 1, stream=None):
+        """Compress a device fp32 weight [out][in] into a packed stack without leaving the device:
+        bitstack_create_stack, bitstack_decompose, bitstack_push_block_device per block."""
+        out, inn = W.shape
+        self = cls.empty(out, inn, n, s, k=k, max_batch=max_batch, device=W.device, stream=stream)
+        sw, U, V = decompose(W, s, n, k=k, iterations=iterations, stream=stream)
+        for i in range(n):
+            self.push_block_device(sw[i], U[i], V[i], stream=stream)
+        import torch
+        (stream or torch.cuda.current_stream(W.device)).synchronize()   # sw, U, V are released on return
+        return self
+
     def push_block(self, sign_words, U, V, stream=None):
         """Stages the block in pinned host memory (kept alive here) and enqueues its load."""
         import torch
@@ -302,6 +317,11 @@ class PackedStack:
         if not hasattr(self, "_staged"):
             self._staged = []
         self._staged.append(pinned)
+
+    def push_block_device(self, sign_words, U, V, stream=None):
+        """bitstack_push_block_device: one block from device tensors in the canonical layout."""
+        _check(lib().bitstack_push_block_device(self._h, sign_words.data_ptr(), U.data_ptr(), V.data_ptr(),
+                                                self._stream(stream)), "bitstack_push_block_device")
 
     def pop_block(self):
         _check(lib().bitstack_pop_block(self._h), "bitstack_pop_block")

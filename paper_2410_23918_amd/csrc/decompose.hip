@@ -476,4 +476,52 @@ hipError_t launch_decompose(const float* W, const float* s, int out, int in, int
     return hipGetLastError();
 }
 
+// One block from canonical device arrays (what launch_decompose writes) into its slot of a packed
+// image: sign words re-tiled, V into panel order, U copied, and the per-channel maxima of V.
+// The same index functions as the host-side packer; the result is byte for byte the same.
+__global__ __launch_bounds__(256) void k_pack_signs(const uint32_t* csw, uint32_t* dsw, int out, int in) {
+    const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
+    const int wpr = in / 32;
+    if (i >= size_t(out) * wpr) return;
+    const int o = int(i / wpr), w = int(i % wpr);
+    dsw[sign_word_index(in, o, w)] = csw[i];
+}
+
+__global__ __launch_bounds__(256) void k_pack_factors(const uint16_t* cu, const uint16_t* cv, uint16_t* du, uint16_t* dv,
+                                                      uint16_t* vm, int out, int in) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < in) {
+        uint16_t m = 0;
+#pragma unroll
+        for (int r = 0; r < kRank; ++r) {
+            const uint16_t h = cv[size_t(i) * kRank + r];
+            dv[v_index(i, r)] = h;
+            uint16_t a = h & 0x7FFFu;
+            if (a > 0x7C00u) a = 0x7C00u;   // NaN payloads: treat as infinity
+            if (a > m) m = a;
+        }
+        vm[panel_index(i)] = m;
+    }
+    if (i < out) {
+        const uint4* src = reinterpret_cast<const uint4*>(cu + size_t(i) * kRank);
+        uint4* dst = reinterpret_cast<uint4*>(du + size_t(i) * kRank);
+        dst[0] = src[0];
+        dst[1] = src[1];
+    }
+}
+
+hipError_t launch_pack_block_device(const Geometry& g, unsigned char* image, int slot, const uint32_t* csw,
+                                    const uint16_t* cu, const uint16_t* cv, hipStream_t st) {
+    unsigned char* blk = image + g.off_blocks + size_t(slot) * g.block_stride;
+    uint16_t* vm = reinterpret_cast<uint16_t*>(image + g.off_vmax) + size_t(slot) * g.in;
+    const size_t words = size_t(g.out) * (g.in / 32);
+    hipLaunchKernelGGL(k_pack_signs, dim3(unsigned((words + 255) / 256)), dim3(256), 0, st, csw,
+                       reinterpret_cast<uint32_t*>(blk), g.out, g.in);
+    const int mx = g.out > g.in ? g.out : g.in;
+    hipLaunchKernelGGL(k_pack_factors, dim3((mx + 255) / 256), dim3(256), 0, st, cu, cv,
+                       reinterpret_cast<uint16_t*>(blk + g.off_u), reinterpret_cast<uint16_t*>(blk + g.off_v), vm, g.out,
+                       g.in);
+    return hipGetLastError();
+}
+
 }  // namespace bitstack

@@ -236,6 +236,20 @@ int bitstack_push_block(bitstack_weight_t* w, const void* staging, bitstack_stre
     return BITSTACK_OK;
 }
 
+int bitstack_push_block_device(bitstack_weight_t* w, const uint32_t* sign_words, const uint16_t* U, const uint16_t* V,
+                               bitstack_stream_t stream) {
+    if (!w || !sign_words || !U || !V) return BITSTACK_E_NULL;
+    const Geometry& g = w->geo;
+    if (w->resident >= g.n) return BITSTACK_E_RANGE;
+    if (reinterpret_cast<uintptr_t>(sign_words) % 4 || reinterpret_cast<uintptr_t>(U) % 16 ||
+        reinterpret_cast<uintptr_t>(V) % 2)
+        return BITSTACK_E_ALIGN;
+    hipError_t e = launch_pack_block_device(g, w->dev, w->resident, sign_words, U, V, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    ++w->resident;
+    return BITSTACK_OK;
+}
+
 int bitstack_pop_block(bitstack_weight_t* w) {
     if (!w) return BITSTACK_E_NULL;
     if (w->resident < 1) return BITSTACK_E_RANGE;

@@ -44,6 +44,9 @@ size_t decompose_workspace_bytes(int out, int in, int slices);
 int decompose_slices(int out, int in);
 hipError_t launch_decompose(const float* W, const float* s, int out, int in, int n, int iters, uint32_t* sign_words,
                             __half* U, __half* V, unsigned char* workspace, hipStream_t st);
+// one block from canonical device arrays into slot `slot` of a packed image (same bytes as the host packer)
+hipError_t launch_pack_block_device(const Geometry& g, unsigned char* image, int slot, const uint32_t* sign_words,
+                                    const uint16_t* U, const uint16_t* V, hipStream_t st);
 // column split the small-batch kernel uses for this shape (1 = none)
 int small_batch_split(int out, int in, int batch, int part_slots);
 

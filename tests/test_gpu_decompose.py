@@ -94,6 +94,10 @@ def test_device_decomposition_matches_the_oracles(B, config, out, inn, n):
     torch.cuda.synchronize()
     err = O.relative_error(y.float().cpu().numpy()[None], O.forward_dense(st, x, n))
     assert err <= 2e-3
+    # the same without the host in between: compress on the device, blocks pushed from device arrays
+    ps2 = B.PackedStack.from_dense(Wd, s, n)
+    assert ps2.resident_blocks == n
+    assert torch.equal(ps2.linear(torch.from_numpy(x[0]).to("cuda:0"), n), y)
     # and it approximates W x as well as the oracle's stack does
     exact = (x.astype(np.float64) @ np.asarray(Wt, dtype=np.float64).T)
     e_dev = np.linalg.norm(O.forward_dense(st, x, n) - exact) / np.linalg.norm(exact)
@@ -134,6 +138,39 @@ def test_cfg2_device_decomposition_against_full_svd_oracle(B):
     err = O.relative_error(y.float().cpu().numpy()[None], O.forward_dense(st, x, n))
     print(f"cfg2: decode kernel on the device's blocks: rel err {err:.2e}", flush=True)
     assert err <= 2e-3
+
+
+def test_blocks_pushed_from_device_arrays_are_the_host_packers_bytes(B):
+    """bitstack_push_block_device against bitstack_pack_blocks: the block slots and the row maxima
+    of the two images are equal byte for byte, so every kernel sees the same stack."""
+    import torch
+    from _cases import synth_stack
+    out, inn, n = 1056, 768, 3
+    st = synth_stack(3, out, inn, n)
+    host = B.PackedStack(st.sign_words(), st.U, st.V, st.s)
+    dev = B.PackedStack.empty(out, inn, n, st.s)
+    sw = torch.from_numpy(np.ascontiguousarray(st.sign_words()).view(np.int32)).to("cuda:0")
+    U = torch.from_numpy(np.ascontiguousarray(st.U)).to("cuda:0")
+    V = torch.from_numpy(np.ascontiguousarray(st.V)).to("cuda:0")
+    for i in range(n):
+        assert dev.resident_blocks == i
+        dev.push_block_device(sw[i], U[i], V[i])
+    torch.cuda.synchronize()
+    assert dev.resident_blocks == n
+    with pytest.raises(B.BitStackError):
+        dev.push_block_device(sw[0], U[0], V[0])          # no free slot
+    # image layout (include/bitstack.h): 1/s, then the blocks, then the row maxima, each 256-byte aligned
+    al = lambda v: (v + 255) & ~255
+    first = 0
+    last = al(al(inn * 4) + n * B.block_bytes(out, inn)) + n * inn * 2
+    assert torch.equal(host.buf[first:last], dev.buf[first:last])
+    x = acts(3, 1, inn)
+    xd = torch.from_numpy(x[0]).to("cuda:0")
+    assert torch.equal(host.linear(xd, n), dev.linear(xd, n))
+    dev.pop_block()
+    dev.push_block_device(sw[n - 1], U[n - 1], V[n - 1])   # a slot can be refilled
+    torch.cuda.synchronize()
+    assert torch.equal(host.buf[first:last], dev.buf[first:last])
 
 
 def test_decompose_argument_errors(B):
