@@ -118,67 +118,81 @@ __global__ __launch_bounds__(256) void k_dc_mul(const float* R, const float* X, 
     }
 }
 
-// Y = sum of the product's slices (written out), G += Y^T Y in fp64; 32 rows of Y (m x kL) per
-// workgroup, every thread four columns of one row with the loads of all slices in flight
-// together.  G must be zero when the first workgroup arrives: the kernels that consume G clear
-// it.  G == nullptr: only the sum is wanted.
-__global__ __launch_bounds__(256) void k_dc_gram(const float* P, int slices, float* Y, int m, double* G) {
+// Y = sum of the product's slices (written out) and this workgroup's part of Y^T Y in fp64:
+// 128 rows of Y (m x kL) per workgroup in four stages of 32, every thread four columns of one row
+// with the loads of all slices in flight together.  The parts are added up in a fixed order by
+// the kernel that consumes the Gram matrix (no atomics: the decomposition is reproducible bit for
+// bit).  Gpart == nullptr: only the sum is wanted.
+constexpr int kGramRows = 128;
+__global__ __launch_bounds__(256) void k_dc_gram(const float* P, int slices, float* Y, int m, double* Gpart) {
     __shared__ float Ys[32][kL + 1];
     const int tid = threadIdx.x, r = tid >> 3, cq = tid & 7;
-    const int row = blockIdx.x * 32 + r;
-    const size_t n = size_t(m) * kL;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (row < m) {
-        const float* src = P + size_t(row) * kL + 4 * cq;
-        int sl = 0;
-        for (; sl + 4 <= slices; sl += 4) {
-            const float4 a = *reinterpret_cast<const float4*>(src + size_t(sl) * n);
-            const float4 b = *reinterpret_cast<const float4*>(src + size_t(sl + 1) * n);
-            const float4 c = *reinterpret_cast<const float4*>(src + size_t(sl + 2) * n);
-            const float4 d = *reinterpret_cast<const float4*>(src + size_t(sl + 3) * n);
-            v.x += (a.x + b.x) + (c.x + d.x); v.y += (a.y + b.y) + (c.y + d.y);
-            v.z += (a.z + b.z) + (c.z + d.z); v.w += (a.w + b.w) + (c.w + d.w);
-        }
-        for (; sl < slices; ++sl) {
-            const float4 a = *reinterpret_cast<const float4*>(src + size_t(sl) * n);
-            v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
-        }
-        *reinterpret_cast<float4*>(Y + size_t(row) * kL + 4 * cq) = v;
-    }
-    if (G == nullptr) return;   // same for the whole grid
-    Ys[r][4 * cq] = v.x; Ys[r][4 * cq + 1] = v.y; Ys[r][4 * cq + 2] = v.z; Ys[r][4 * cq + 3] = v.w;
-    __syncthreads();
     const int i = tid >> 3, jg = tid & 7;
+    const size_t n = size_t(m) * kL;
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int st = 0; st < kGramRows / 32; ++st) {
+        const int row = blockIdx.x * kGramRows + st * 32 + r;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row < m) {
+            const float* src = P + size_t(row) * kL + 4 * cq;
+            int sl = 0;
+            for (; sl + 4 <= slices; sl += 4) {
+                const float4 a = *reinterpret_cast<const float4*>(src + size_t(sl) * n);
+                const float4 b = *reinterpret_cast<const float4*>(src + size_t(sl + 1) * n);
+                const float4 c = *reinterpret_cast<const float4*>(src + size_t(sl + 2) * n);
+                const float4 d = *reinterpret_cast<const float4*>(src + size_t(sl + 3) * n);
+                v.x += (a.x + b.x) + (c.x + d.x); v.y += (a.y + b.y) + (c.y + d.y);
+                v.z += (a.z + b.z) + (c.z + d.z); v.w += (a.w + b.w) + (c.w + d.w);
+            }
+            for (; sl < slices; ++sl) {
+                const float4 a = *reinterpret_cast<const float4*>(src + size_t(sl) * n);
+                v.x += a.x; v.y += a.y; v.z += a.z; v.w += a.w;
+            }
+            *reinterpret_cast<float4*>(Y + size_t(row) * kL + 4 * cq) = v;
+        }
+        if (Gpart == nullptr) continue;   // same for the whole grid
+        Ys[r][4 * cq] = v.x; Ys[r][4 * cq + 1] = v.y; Ys[r][4 * cq + 2] = v.z; Ys[r][4 * cq + 3] = v.w;
+        __syncthreads();
 #pragma unroll 8
-    for (int q = 0; q < 32; ++q) {
-        const double yi = double(Ys[q][i]);
+        for (int q = 0; q < 32; ++q) {
+            const double yi = double(Ys[q][i]);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] += yi * double(Ys[q][4 * jg + e]);
+            for (int e = 0; e < 4; ++e) acc[e] += yi * double(Ys[q][4 * jg + e]);
+        }
+        __syncthreads();
     }
+    if (Gpart == nullptr) return;
+    double* dst = Gpart + size_t(blockIdx.x) * (kL * kL) + i * kL + 4 * jg;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) atomicAdd(&G[i * kL + 4 * jg + e], acc[e]);
+    for (int e = 0; e < 4; ++e) dst[e] = acc[e];
 }
 
-__global__ __launch_bounds__(256) void k_dc_zero64(double* G, int n) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) G[i] = 0.0;
+// the Gram matrix from its parts, in a fixed order, into LDS (256 threads, four entries each)
+__device__ __forceinline__ void gram_sum(const double* Gpart, int parts, double (*Gs)[kL + 1]) {
+    const int e0 = threadIdx.x * 4;
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    for (int p = 0; p < parts; ++p) {
+        const double* src = Gpart + size_t(p) * (kL * kL) + e0;
+        a0 += src[0]; a1 += src[1]; a2 += src[2]; a3 += src[3];
+    }
+    const int row = e0 / kL, col = e0 % kL;
+    Gs[row][col] = a0; Gs[row][col + 1] = a1; Gs[row][col + 2] = a2; Gs[row][col + 3] = a3;
 }
 
-// G = C^T C (Cholesky, C upper triangular), T = C^-1, so that Y T has orthonormal columns; G is
-// cleared for the next Gram matrix.  One wavefront, fp64: thread t keeps row t of the lower factor
-// in registers, finished rows are published through LDS (one barrier per column).
-__global__ __launch_bounds__(64) void k_dc_chol_inv(double* G, float* T) {
+// G = C^T C (Cholesky, C upper triangular), T = C^-1, so that Y T has orthonormal columns.
+// 256 threads add up the parts of G; then 32 of them factorise in fp64: thread t keeps row t of
+// the lower factor in registers, finished rows are published through LDS (one barrier per column).
+__global__ __launch_bounds__(256) void k_dc_chol_inv(const double* Gpart, int parts, float* T) {
+    __shared__ double Gs[kL][kL + 1];
     __shared__ double Lr[kL][kL + 1];
     const int t = threadIdx.x;
+    gram_sum(Gpart, parts, Gs);
+    __syncthreads();
     double a[kL];
     if (t < kL) {
-        Lr[t][t] = G[t * kL + t];   // the diagonal, for the trace
+        Lr[t][t] = Gs[t][t];   // the diagonal, for the trace
 #pragma unroll
-        for (int c = 0; c < kL; ++c) {
-            a[c] = G[t * kL + c];
-            G[t * kL + c] = 0.0;
-        }
+        for (int c = 0; c < kL; ++c) a[c] = Gs[t][c];
     }
     __syncthreads();
     double tr = 0.0;
@@ -261,21 +275,18 @@ __global__ __launch_bounds__(256) void k_dc_apply(const float* Y, const float* T
 // H diag(sigma^2) H^T gives the leading triplets of |R|: left vectors Q H, right vectors
 // Z H diag(1/sigma).  Tu = H_k diag(sqrt(sigma)), Tv = H_k diag(1/sqrt(sigma)) (Eq. 2's split):
 // U = Q Tu, V = Z Tv.  Jacobi rotations in fp64 in the round-robin ordering: 31 rounds of 16
-// disjoint pairs per sweep, the 16 rotations of a round applied together.  One wavefront; G is
-// cleared for the next Gram matrix.
-__global__ __launch_bounds__(64) void k_dc_ritz(double* G, float* Tu, float* Tv, int k) {
+// disjoint pairs per sweep, the 16 rotations of a round applied together (32 of the 256 threads;
+// all of them add up the parts of G first).
+__global__ __launch_bounds__(256) void k_dc_ritz(const double* Gpart, int parts, float* Tu, float* Tv, int k) {
     __shared__ double A[kL][kL + 1];
     __shared__ double H[kL][kL + 1];
     __shared__ double cs[kL / 2][2];
     __shared__ int pq[kL / 2][2];
     __shared__ int order[kL];
     const int t = threadIdx.x;
+    gram_sum(Gpart, parts, A);
     if (t < kL)
-        for (int c = 0; c < kL; ++c) {
-            A[t][c] = G[t * kL + c];
-            G[t * kL + c] = 0.0;
-            H[t][c] = (t == c) ? 1.0 : 0.0;
-        }
+        for (int c = 0; c < kL; ++c) H[t][c] = (t == c) ? 1.0 : 0.0;
     __syncthreads();
     for (int sweep = 0; sweep < 7; ++sweep) {   // off-diagonal mass falls quadratically: far below fp64 rounding by then
         for (int round = 0; round < kL - 1; ++round) {
@@ -386,7 +397,7 @@ size_t decompose_workspace_bytes(int out, int in, int slices) {
     b += 2 * align256(size_t(out) * kL * 4);                 // Y, Q (out side)
     b += 2 * align256(size_t(in) * kL * 4);                  // Z, Qz (in side)
     b += align256(size_t(slices) * mx * kL * 4);             // partial products
-    b += align256(kL * kL * 8) + 3 * align256(kL * kL * 4);  // G, T, Tu, Tv
+    b += align256(((mx + kGramRows - 1) / kGramRows) * size_t(kL * kL * 8)) + 3 * align256(kL * kL * 4);  // Gram parts, T, Tu, Tv
     return b;
 }
 
@@ -414,7 +425,7 @@ hipError_t launch_decompose(const float* W, const float* s, int out, int in, int
     float* Z = reinterpret_cast<float*>(take(size_t(in) * kL * 4));
     float* Qz = reinterpret_cast<float*>(take(size_t(in) * kL * 4));
     float* P = reinterpret_cast<float*>(take(size_t(slices) * mx * kL * 4));
-    double* G = reinterpret_cast<double*>(take(kL * kL * 8));
+    double* G = reinterpret_cast<double*>(take(((mx + kGramRows - 1) / kGramRows) * size_t(kL * kL * 8)));
     float* T = reinterpret_cast<float*>(take(kL * kL * 4));
     float* Tu = reinterpret_cast<float*>(take(kL * kL * 4));
     float* Tv = reinterpret_cast<float*>(take(kL * kL * 4));
@@ -422,7 +433,6 @@ hipError_t launch_decompose(const float* W, const float* s, int out, int in, int
     const size_t total = size_t(out) * in;
     hipLaunchKernelGGL(k_dc_scale, dim3(unsigned((total + 255) / 256)), dim3(256), 0, st, W, s, R, total, in);
 
-    hipLaunchKernelGGL(k_dc_zero64, dim3(4), dim3(256), 0, st, G, kL * kL);
     // P = slices of |R| X  (X: in x kL)  or of  |R|^T X  (X: out x kL)
     auto mul = [&](bool trans, const float* X) {
         const int M = trans ? in : out, K = trans ? out : in;
@@ -437,12 +447,13 @@ hipError_t launch_decompose(const float* W, const float* s, int out, int in, int
     // the product in P, added up into raw (m x kL), columns made orthonormal into dst: Cholesky
     // QR with the Gram matrix in fp64; a second pass (twice = orthonormal to rounding) where asked
     auto orth = [&](float* raw, float* dst, int m, bool twice) {
-        hipLaunchKernelGGL(k_dc_gram, dim3((m + 31) / 32), dim3(256), 0, st, P, slices, raw, m, G);
-        hipLaunchKernelGGL(k_dc_chol_inv, dim3(1), dim3(64), 0, st, G, T);
+        const int parts = (m + kGramRows - 1) / kGramRows;
+        hipLaunchKernelGGL(k_dc_gram, dim3(parts), dim3(256), 0, st, P, slices, raw, m, G);
+        hipLaunchKernelGGL(k_dc_chol_inv, dim3(1), dim3(256), 0, st, G, parts, T);
         hipLaunchKernelGGL((k_dc_apply<kL, false>), dim3((m + 255) / 256), dim3(256), 0, st, raw, T, dst, m);
         if (twice) {
-            hipLaunchKernelGGL(k_dc_gram, dim3((m + 31) / 32), dim3(256), 0, st, dst, 1, raw, m, G);
-            hipLaunchKernelGGL(k_dc_chol_inv, dim3(1), dim3(64), 0, st, G, T);
+            hipLaunchKernelGGL(k_dc_gram, dim3(parts), dim3(256), 0, st, dst, 1, raw, m, G);
+            hipLaunchKernelGGL(k_dc_chol_inv, dim3(1), dim3(256), 0, st, G, parts, T);
             hipLaunchKernelGGL((k_dc_apply<kL, false>), dim3((m + 255) / 256), dim3(256), 0, st, raw, T, dst, m);
         }
     };
@@ -462,13 +473,13 @@ hipError_t launch_decompose(const float* W, const float* s, int out, int in, int
         // between spreads the columns' lengths by sigma_0 / sigma_31 ~ 30, far inside fp32)
         for (int it = 0; it < iters; ++it) {
             mul(true, Q);
-            hipLaunchKernelGGL(k_dc_gram, dim3((in + 31) / 32), dim3(256), 0, st, P, slices, Z, in, static_cast<double*>(nullptr));
+            hipLaunchKernelGGL(k_dc_gram, dim3((in + kGramRows - 1) / kGramRows), dim3(256), 0, st, P, slices, Z, in, static_cast<double*>(nullptr));
             mul(false, Z);
             orth(Y, Q, out, it == iters - 1);
         }
         mul(true, Q);
-        hipLaunchKernelGGL(k_dc_gram, dim3((in + 31) / 32), dim3(256), 0, st, P, slices, Z, in, G);
-        hipLaunchKernelGGL(k_dc_ritz, dim3(1), dim3(64), 0, st, G, Tu, Tv, kRank);
+        hipLaunchKernelGGL(k_dc_gram, dim3((in + kGramRows - 1) / kGramRows), dim3(256), 0, st, P, slices, Z, in, G);
+        hipLaunchKernelGGL(k_dc_ritz, dim3(1), dim3(256), 0, st, G, (in + kGramRows - 1) / kGramRows, Tu, Tv, kRank);
         hipLaunchKernelGGL((k_dc_apply<kRank, true>), dim3((out + 255) / 256), dim3(256), 0, st, Q, Tu, Ui, out);
         hipLaunchKernelGGL((k_dc_apply<kRank, true>), dim3((in + 255) / 256), dim3(256), 0, st, Z, Tv, Vi, in);
         hipLaunchKernelGGL(k_dc_update, dim3((in + 63) / 64, (out + 31) / 32), dim3(256), 0, st, R, Ui, Vi, out, in);

@@ -50,6 +50,9 @@ def test_device_decomposition_matches_the_oracles(B, config, out, inn, n):
     Wd = torch.from_numpy(np.ascontiguousarray(Wt, dtype=np.float32)).to("cuda:0")
     sw, U, V = B.decompose(Wd, s, n)
     torch.cuda.synchronize()
+    # reproducible bit for bit (no atomics anywhere in the decomposition)
+    sw_b, U_b, V_b = B.decompose(Wd, s, n)
+    assert torch.equal(sw, sw_b) and torch.equal(U, U_b) and torch.equal(V, V_b)
     sw = sw.cpu().numpy().view(np.uint32)
     U = U.cpu().numpy()
     V = V.cpu().numpy()
