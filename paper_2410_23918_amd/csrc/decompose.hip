@@ -171,7 +171,22 @@ __global__ __launch_bounds__(256) void k_dc_gram(const float* P, int slices, flo
 __device__ __forceinline__ void gram_sum(const double* Gpart, int parts, double (*Gs)[kL + 1]) {
     const int e0 = threadIdx.x * 4;
     double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-    for (int p = 0; p < parts; ++p) {
+    typedef double d2 __attribute__((ext_vector_type(2)));
+    int p = 0;
+    for (; p + 4 <= parts; p += 4) {   // four parts' loads in flight together; the order of the additions is fixed
+        d2 lo[4], hi[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const d2* src = reinterpret_cast<const d2*>(Gpart + size_t(p + u) * (kL * kL) + e0);
+            lo[u] = src[0];
+            hi[u] = src[1];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            a0 += lo[u][0]; a1 += lo[u][1]; a2 += hi[u][0]; a3 += hi[u][1];
+        }
+    }
+    for (; p < parts; ++p) {
         const double* src = Gpart + size_t(p) * (kL * kL) + e0;
         a0 += src[0]; a1 += src[1]; a2 += src[2]; a3 += src[3];
     }
@@ -188,6 +203,7 @@ __global__ __launch_bounds__(256) void k_dc_chol_inv(const double* Gpart, int pa
     const int t = threadIdx.x;
     gram_sum(Gpart, parts, Gs);
     __syncthreads();
+    if (t >= 64) return;   // the factorisation is one wavefront's work; its barriers then cost little
     double a[kL];
     if (t < kL) {
         Lr[t][t] = Gs[t][t];   // the diagonal, for the trace
@@ -288,6 +304,7 @@ __global__ __launch_bounds__(256) void k_dc_ritz(const double* Gpart, int parts,
     if (t < kL)
         for (int c = 0; c < kL; ++c) H[t][c] = (t == c) ? 1.0 : 0.0;
     __syncthreads();
+    if (t >= 64) return;   // the rotations are one wavefront's work
     for (int sweep = 0; sweep < 7; ++sweep) {   // off-diagonal mass falls quadratically: far below fp64 rounding by then
         for (int round = 0; round < kL - 1; ++round) {
             if (t < kL / 2) {
