@@ -739,11 +739,35 @@ static hipError_t launch_decode_t(KGroup& grp, int bg_req, hipStream_t st) {
         p.n_ks = p.in / KS;
         total_pairs += p.n_rs * p.n_ks;
     }
+    // Merged launches: the stacks of a group differ in height (Section 2.2: the sorted universal
+    // stack leaves every weight stack its own number of blocks), and the launch lasts as long as
+    // its slowest workgroup.  So every stack gets block groups in proportion to its height:
+    // the smallest number of blocks per workgroup T for which all workgroups still fit on the
+    // chip in one round, and ceil(n_loaded / T) groups per stack.
+    int blocks_per_wg = 0;
+    if (grp.count > 1 && bg_req <= 0) {
+        long work = 0;
+        int tallest = 1;
+        for (int i = 0; i < grp.count; ++i) {
+            work += long(grp.s[i].n_rs) * grp.s[i].n_ks * grp.s[i].n_loaded;
+            tallest = tallest > grp.s[i].n_loaded ? tallest : grp.s[i].n_loaded;
+        }
+        for (int t = int((work + 255) / 256); t <= tallest; ++t) {
+            long wgs = 0;
+            for (int i = 0; i < grp.count; ++i)
+                wgs += long(grp.s[i].n_rs) * grp.s[i].n_ks * ((grp.s[i].n_loaded + t - 1) / t);
+            blocks_per_wg = t;
+            if (wgs <= 256) break;
+        }
+        if (blocks_per_wg < 1) blocks_per_wg = 1;
+    }
     unsigned next = 0;
     for (int i = 0; i < grp.count; ++i) {
         KParams& p = grp.s[i];
         int bg = bg_req;
-        if (bg <= 0) {
+        if (blocks_per_wg > 0) {
+            bg = (p.n_loaded + blocks_per_wg - 1) / blocks_per_wg;
+        } else if (bg <= 0) {
             // largest group count that still fits on the chip in one round; among those prefer
             // one that gives every workgroup the same number of blocks
             bg = 256 / total_pairs;
