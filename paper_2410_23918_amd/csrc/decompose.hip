@@ -305,7 +305,22 @@ __global__ __launch_bounds__(256) void k_dc_ritz(const double* Gpart, int parts,
         for (int c = 0; c < kL; ++c) H[t][c] = (t == c) ? 1.0 : 0.0;
     __syncthreads();
     if (t >= 64) return;   // the rotations are one wavefront's work
-    for (int sweep = 0; sweep < 7; ++sweep) {   // off-diagonal mass falls quadratically: far below fp64 rounding by then
+    __shared__ double offd[kL];
+    for (int sweep = 0; sweep < 10; ++sweep) {
+        // converged?  (off-diagonal mass against the trace; falls quadratically once small)
+        if (t < kL) {
+            double o = 0.0;
+            for (int c = 0; c < kL; ++c) o += (c == t) ? 0.0 : A[t][c] * A[t][c];
+            offd[t] = o;
+        }
+        __syncthreads();
+        double off = 0.0, tr = 0.0;
+        for (int c = 0; c < kL; ++c) {
+            off += offd[c];
+            tr += fabs(A[c][c]);
+        }
+        __syncthreads();
+        if (off <= 1e-26 * tr * tr) break;   // same for every thread
         for (int round = 0; round < kL - 1; ++round) {
             if (t < kL / 2) {
                 // pair t of this round: (kL - 1, round) and ((round + t) mod 31, (round - t) mod 31)
@@ -330,26 +345,45 @@ __global__ __launch_bounds__(256) void k_dc_ritz(const double* Gpart, int parts,
                 cs[t][1] = s;
             }
             __syncthreads();
+            // the 16 pairs are disjoint: all reads of a phase first (in flight together), then the writes
+            int pp[kL / 2], qq[kL / 2];
+            double cc[kL / 2], ss[kL / 2];
+#pragma unroll
+            for (int e = 0; e < kL / 2; ++e) {
+                pp[e] = pq[e][0];
+                qq[e] = pq[e][1];
+                cc[e] = cs[e][0];
+                ss[e] = cs[e][1];
+            }
             if (t < kL) {   // columns p, q of A and H for every pair: row t
+                double ap[kL / 2], aq[kL / 2], hp[kL / 2], hq[kL / 2];
+#pragma unroll
                 for (int e = 0; e < kL / 2; ++e) {
-                    const int p = pq[e][0], q = pq[e][1];
-                    const double c = cs[e][0], s = cs[e][1];
-                    const double ap = A[t][p], aq = A[t][q];
-                    A[t][p] = c * ap - s * aq;
-                    A[t][q] = s * ap + c * aq;
-                    const double hp = H[t][p], hq = H[t][q];
-                    H[t][p] = c * hp - s * hq;
-                    H[t][q] = s * hp + c * hq;
+                    ap[e] = A[t][pp[e]];
+                    aq[e] = A[t][qq[e]];
+                    hp[e] = H[t][pp[e]];
+                    hq[e] = H[t][qq[e]];
+                }
+#pragma unroll
+                for (int e = 0; e < kL / 2; ++e) {
+                    A[t][pp[e]] = cc[e] * ap[e] - ss[e] * aq[e];
+                    A[t][qq[e]] = ss[e] * ap[e] + cc[e] * aq[e];
+                    H[t][pp[e]] = cc[e] * hp[e] - ss[e] * hq[e];
+                    H[t][qq[e]] = ss[e] * hp[e] + cc[e] * hq[e];
                 }
             }
             __syncthreads();
             if (t < kL) {   // rows p, q of A for every pair: column t
+                double ap[kL / 2], aq[kL / 2];
+#pragma unroll
                 for (int e = 0; e < kL / 2; ++e) {
-                    const int p = pq[e][0], q = pq[e][1];
-                    const double c = cs[e][0], s = cs[e][1];
-                    const double ap = A[p][t], aq = A[q][t];
-                    A[p][t] = c * ap - s * aq;
-                    A[q][t] = s * ap + c * aq;
+                    ap[e] = A[pp[e]][t];
+                    aq[e] = A[qq[e]][t];
+                }
+#pragma unroll
+                for (int e = 0; e < kL / 2; ++e) {
+                    A[pp[e]][t] = cc[e] * ap[e] - ss[e] * aq[e];
+                    A[qq[e]][t] = ss[e] * ap[e] + cc[e] * aq[e];
                 }
             }
             __syncthreads();
