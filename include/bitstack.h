@@ -10,7 +10,9 @@
  *
  *     y = ( sum_{i < n_loaded} S_i (.) (U_i V_i^T) ) diag(1/s) x        (Eq. 4, Eq. 8)
  *
- * without ever writing the reconstructed weight to device memory.
+ * without writing the reconstructed weight to device memory (the optional
+ * materialising path further down restores it into a scratch buffer the caller
+ * lends for the duration of a call).
  * (Paper orientation: X (p x m), W (m x n), Y = X W; here out = n_paper,
  *  in = m_paper, U = B', V = A', S = W_sign^T.)
  *
