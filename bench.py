@@ -172,7 +172,7 @@ def batch_table(B, torch, dev, n):
     return rows
 
 
-def decompose_table(B, torch, dev, iterations=20):
+def decompose_table(B, torch, dev, iterations=16):
     """The decomposition on the device (bitstack_decompose): time per residual block at the 4096x4096
     and 14336x4096 shapes.  Algorithmic bytes per block: the fp32 residual is read once by each of
     the 2 * iterations + 2 tall products and by the sign packing, and read and written once by the

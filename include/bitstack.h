@@ -255,7 +255,8 @@ int bitstack_linear_materialised(const void* x, int batch, const bitstack_weight
  *     U_i V_i^T = the top-k singular triplets of |R_i| with sqrt(sigma) on either side (Eq. 2),
  *     rounded to fp16;   R_{i+1} = R_i - S_i (.) (U_i V_i^T)  with the factors as stored.
  * The singular triplets come from a block power (subspace) iteration with k + 16 columns and
- * `iterations` rounds (0 = 20; one round applies |R| |R|^T once) followed by a Rayleigh-Ritz step, in fp32 (small Gram and
+ * `iterations` rounds (0 = 16; one round applies |R| |R|^T once; the residual norm after a block
+ * exceeds the exact truncation's by ~3e-4 / 7e-5 / 2e-5 / 8e-6 relative with 8 / 12 / 16 / 20 rounds) followed by a Rayleigh-Ritz step, in fp32 (small Gram and
  * eigenvalue problems in fp64).
  *   W: device fp32 [out][in] row-major, 16-byte aligned (not modified).
  *   s: HOST fp32 [in], every entry finite and > 0 (BITSTACK_E_SCALE otherwise); copied to the

@@ -504,7 +504,7 @@ int bitstack_decompose(const float* W, const float* s, int out, int in, int k, i
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     BS_HIP(hipMemcpyAsync(ws, s, size_t(in) * 4, hipMemcpyHostToDevice, st));
     if (n == 0) return BITSTACK_OK;
-    hipError_t e = launch_decompose(W, reinterpret_cast<const float*>(ws), out, in, n, iterations ? iterations : 20, sign_words,
+    hipError_t e = launch_decompose(W, reinterpret_cast<const float*>(ws), out, in, n, iterations ? iterations : 16, sign_words,
                                     reinterpret_cast<__half*>(U), reinterpret_cast<__half*>(V),
                                     ws + align256(size_t(in) * 4), st);
     if (e != hipSuccess) return hip_fail(e);
