@@ -268,6 +268,41 @@ def test_job_list_merging_rules(B):
         assert torch.equal(got[k], want), k
 
 
+def test_degenerate_activations(B):
+    """x = 0 gives y = 0 exactly (the panel's quantisation scale is zero: nothing may divide by
+    it); a one-hot x picks one column of W' diag(1/s); a huge and a tiny x keep the relative error
+    (the panel is quantised against its own maximum per block and column slab)."""
+    import torch
+    out, inn, n = 1056, 2048, 3
+    st = synth_stack(3, out, inn, n)
+    ps = _pack(B, st, max_batch=40)
+    zero = np.zeros((1, inn), dtype=np.float16)
+    for kern in (B.KERNEL_DECODE, B.KERNEL_PANEL, B.KERNEL_REFERENCE):
+        y = _run(B, ps, zero, n, kern)
+        assert not y.any() and np.isfinite(y).all()
+    hot = np.zeros((3, inn), dtype=np.float16)
+    hot[0, 0] = 1.0
+    hot[1, 1023] = -2.5
+    hot[2, inn - 1] = 0.125
+    ref = O.forward_dense(st, hot, n)
+    for kern in (B.KERNEL_DECODE, B.KERNEL_PANEL):
+        y = _run(B, ps, hot, n, kern)
+        err = O.relative_error(y, ref)
+        print(f"one-hot activations, kernel {kern}: {err:.2e}", flush=True)
+        assert err <= TOL
+    x = acts(3, 1, inn)
+    for scale in (2.0 ** -14, 2.0 ** 10):
+        xs = (x.astype(np.float32) * scale).astype(np.float16)
+        want = O.forward_dense(st, xs, n)
+        if np.abs(want).max() < 6.0e4:                      # stays inside fp16's range
+            y = _run(B, ps, xs, n, B.KERNEL_DECODE)
+            err = O.relative_error(y, want)
+            print(f"activations scaled by {scale:g}: {err:.2e}", flush=True)
+            assert err <= TOL
+        y32 = _run(B, ps, xs, n, B.KERNEL_DECODE, "f32")
+        assert O.relative_error(y32, want) <= TOL
+
+
 def test_argument_errors_on_device(B):
     import torch
     st = synth_stack(3, 32, 256, 1)
