@@ -303,6 +303,33 @@ def test_degenerate_activations(B):
         assert O.relative_error(y32, want) <= TOL
 
 
+def test_two_stacks_on_two_streams(B):
+    """Calls on different handles may overlap in time (each image has its own workspace and
+    counters; the library keeps no per-call state of its own): two stacks driven from two streams
+    give the same bits as one after the other."""
+    import torch
+    a = synth_stack(3, 1056, 2048, 3)
+    b = synth_stack(3, 2048, 1024, 4, tag=1)
+    pa, pb = _pack(B, a), _pack(B, b)
+    xa = torch.from_numpy(acts(3, 1, 2048)[0]).to("cuda:0")
+    xb = torch.from_numpy(acts(3, 1, 1024, tag=1)[0]).to("cuda:0")
+    ya_ref = pa.linear(xa, 3).clone()
+    yb_ref = pb.linear(xb, 4).clone()
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()      # default priority
+    ya = [torch.empty_like(ya_ref) for _ in range(20)]
+    yb = [torch.empty_like(yb_ref) for _ in range(20)]
+    for i in range(20):
+        pa.linear(xa, 3, y=ya[i], stream=s1)
+        pb.linear(xb, 4, y=yb[i], stream=s2)
+    s1.synchronize()
+    s2.synchronize()
+    for i in range(20):
+        assert torch.equal(ya[i], ya_ref) and torch.equal(yb[i], yb_ref)
+    err = O.relative_error(ya_ref.float().cpu().numpy()[None], O.forward_dense(a, acts(3, 1, 2048), 3))
+    assert err <= TOL
+
+
 def test_argument_errors_on_device(B):
     import torch
     st = synth_stack(3, 32, 256, 1)
