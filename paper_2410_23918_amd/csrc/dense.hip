@@ -18,7 +18,8 @@
 // 128-bit reads) and issues eight v_mfma_f32_32x32x16_f16; the other wavefront of the SIMD covers
 // the read latency.  One LDS-only barrier per chunk.  The fp16 output tile is turned in LDS and
 // leaves in 16-byte pieces.  Workgroup ids map to tiles so that all token tiles of a row tile run
-// on one XCD (one L2 pulls that part of the weight).
+// on one XCD (one L2 pulls that part of the weight).  A second instantiation with 128-row tiles
+// fills the chip for shapes with few row tiles (chosen per launch on the host).
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -31,7 +32,7 @@ namespace bitstack {
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
-constexpr int kGemmRows = 256;              // output rows per workgroup
+constexpr int kGemmRows = 256;              // output rows per workgroup (128 in the narrow variant)
 constexpr int kGemmTokens = 256;            // tokens per workgroup
 constexpr int kGemmKc = 64;                 // input columns per chunk
 constexpr int kGemmLd = kGemmKc + 8;        // fp16 per LDS row (+8: bank spread for 128-bit reads)
@@ -45,26 +46,31 @@ __global__ __launch_bounds__(256) void k_dense_zero(uint4* w, size_t n16) {
     if (i < n16) w[i] = make_uint4(0, 0, 0, 0);
 }
 
+// RJ: 32-row fragments per wavefront.  4: the 256-row tile described above.  2: a 128-row tile
+// (wavefront tile 64 rows x 64 tokens, four matrix instructions per step), for shapes whose
+// 256-row tiles would leave half of the compute units without a workgroup.
+template <int RJ>
 __global__ __launch_bounds__(512) void k_gemm(KParams p) {
+    constexpr int ROWS = 64 * RJ;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     _Float16* const wl = reinterpret_cast<_Float16*>(smem);   // [buffer][256 rows][kGemmLd]
     _Float16* const xl = wl + 2 * kGemmTile;                   // [buffer][256 tokens][kGemmLd]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hl = lane >> 5, ln = lane & 31;
-    const int tg = wave & 3, rg = wave >> 2;   // my 64 tokens and 128 rows inside the workgroup's tile
+    const int tg = wave & 3, rg = wave >> 2;   // my 64 tokens and 32 RJ rows inside the workgroup's tile
 
     // Workgroup ids are dealt round-robin to the 8 XCDs: all token tiles of a row tile go to one
     // XCD, so that a weight tile is pulled into one L2 only.
-    const int ntt = (p.batch + kGemmTokens - 1) / kGemmTokens, nrt = (p.out + kGemmRows - 1) / kGemmRows;
+    const int ntt = (p.batch + kGemmTokens - 1) / kGemmTokens, nrt = (p.out + ROWS - 1) / ROWS;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int rt = xcd + 8 * (slot / ntt), tt = slot % ntt;
     if (rt >= nrt) return;
-    const int row0 = rt * kGemmRows, tok0 = tt * kGemmTokens;
+    const int row0 = rt * ROWS, tok0 = tt * kGemmTokens;
     const int nkc = p.in / kGemmKc;   // a multiple of 4
 
-    // both tiles of a chunk: thread (row tid/8 + 64 i, 16-byte piece tid%8), i = 0..3; rows and
-    // tokens past the end repeat the last one (computed, never stored)
+    // both tiles of a chunk: thread (row tid/8 + 64 i, 16-byte piece tid%8), i = 0..3 (weight
+    // rows: i < RJ); rows and tokens past the end repeat the last one (computed, never stored)
     const unsigned char* const wbase = reinterpret_cast<const unsigned char*>(p.wdense);
     const unsigned char* const xbase = reinterpret_cast<const unsigned char*>(p.x);
     // (scalar variables and macros on purpose: arrays or structs of 128 bytes of load results
@@ -88,8 +94,10 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
         const unsigned c = unsigned(min((KC), nkc - 1)) * (kGemmKc * 2);                   \
         w##S##0 = ld16(wbase, wo0 + c);                                                    \
         w##S##1 = ld16(wbase, wo1 + c);                                                    \
-        w##S##2 = ld16(wbase, wo2 + c);                                                    \
-        w##S##3 = ld16(wbase, wo3 + c);                                                    \
+        if constexpr (RJ == 4) {                                                           \
+            w##S##2 = ld16(wbase, wo2 + c);                                                \
+            w##S##3 = ld16(wbase, wo3 + c);                                                \
+        }                                                                                  \
         x##S##0 = ld16(xbase, xo0 + c);                                                    \
         x##S##1 = ld16(xbase, xo1 + c);                                                    \
         x##S##2 = ld16(xbase, xo2 + c);                                                    \
@@ -99,15 +107,17 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
     {                                                                                      \
         st16(wl, BUF, 0, w##S##0);                                                         \
         st16(wl, BUF, 1, w##S##1);                                                         \
-        st16(wl, BUF, 2, w##S##2);                                                         \
-        st16(wl, BUF, 3, w##S##3);                                                         \
+        if constexpr (RJ == 4) {                                                           \
+            st16(wl, BUF, 2, w##S##2);                                                     \
+            st16(wl, BUF, 3, w##S##3);                                                     \
+        }                                                                                  \
         st16(xl, BUF, 0, x##S##0);                                                         \
         st16(xl, BUF, 1, x##S##1);                                                         \
         st16(xl, BUF, 2, x##S##2);                                                         \
         st16(xl, BUF, 3, x##S##3);                                                         \
     }
     // fragments of step s (16 columns) of the chunk in buffer buf: weight rows j*32.., tokens t*32..
-    const _Float16* const wfr = wl + (rg * 128 + ln) * kGemmLd + 8 * hl;
+    const _Float16* const wfr = wl + (rg * (32 * RJ) + ln) * kGemmLd + 8 * hl;
     const _Float16* const xfr = xl + (tg * 64 + ln) * kGemmLd + 8 * hl;
     auto wfrag = [&](int buf, int s, int j) -> v8h {
         return *reinterpret_cast<const v8h*>(wfr + buf * kGemmTile + j * 32 * kGemmLd + s * 16);
@@ -116,15 +126,15 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
         return *reinterpret_cast<const v8h*>(xfr + buf * kGemmTile + t * 32 * kGemmLd + s * 16);
     };
 
-    v16f acc[4][2];   // [row fragment][token group]
+    v16f acc[RJ][2];   // [row fragment][token group]
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < RJ; ++j)
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][t][v] = 0.0f;
 
-    uint4 wA0, wA1, wA2, wA3, xA0, xA1, xA2, xA3, wB0, wB1, wB2, wB3, xB0, xB1, xB2, xB3;
+    uint4 wA0, wA1, wA2 = {}, wA3 = {}, xA0, xA1, xA2, xA3, wB0, wB1, wB2 = {}, wB3 = {}, xB0, xB1, xB2, xB3;
     BS_GEMM_LOAD(A, 0)
     BS_GEMM_LOAD(B, 1)
     BS_GEMM_WRITE(A, 0)
@@ -143,11 +153,11 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
                 BS_GEMM_WRITE(S, (BUF) ^ 1)                                                \
                 BS_GEMM_LOAD(S, (KC) + 3)                                                  \
             }                                                                              \
-            v8h b[4], a[2];                                                                \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j) b[j] = wfrag(BUF, s, j);         \
+            v8h b[RJ], a[2];                                                               \
+            _Pragma("unroll") for (int j = 0; j < RJ; ++j) b[j] = wfrag(BUF, s, j);        \
             _Pragma("unroll") for (int t = 0; t < 2; ++t) a[t] = xfrag(BUF, s, t);         \
             __builtin_amdgcn_sched_barrier(0); /* requests before the step's arithmetic */ \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                \
+            _Pragma("unroll") for (int j = 0; j < RJ; ++j) {                               \
                 acc[j][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], b[j], acc[j][0], 0, 0, 0); \
                 acc[j][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[1], b[j], acc[j][1], 0, 0, 0); \
             }                                                                              \
@@ -166,34 +176,35 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
     // C[i = token][n = row]: lane (row ln), register v holds token 8*(v/4) + 4*hl + v%4 of the group
     if (p.y_f32) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < RJ; ++j)
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int tok = tok0 + tg * 64 + t * 32 + 8 * (v >> 2) + 4 * hl + (v & 3);
-                    const int row = row0 + rg * 128 + j * 32 + ln;
+                    const int row = row0 + rg * (32 * RJ) + j * 32 + ln;
                     if (tok < p.batch && row < p.out) static_cast<float*>(p.y)[size_t(tok) * p.out + row] = acc[j][t][v];
                 }
         return;
     }
     // fp16 output: the tile is turned in LDS (the operand buffers are free now; the loop's last
-    // barrier has passed) so that it leaves in 16-byte pieces, 512 contiguous bytes per token,
+    // barrier has passed) so that it leaves in 16-byte pieces, 2 ROWS contiguous bytes per token,
     // instead of 2-byte pieces
     _Float16* const yl = reinterpret_cast<_Float16*>(smem);   // [256 tokens][kGemmYLd]
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < RJ; ++j)
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-                yl[(tg * 64 + t * 32 + 8 * (v >> 2) + 4 * hl + (v & 3)) * kGemmYLd + rg * 128 + j * 32 + ln] =
+                yl[(tg * 64 + t * 32 + 8 * (v >> 2) + 4 * hl + (v & 3)) * kGemmYLd + rg * (32 * RJ) + j * 32 + ln] =
                     _Float16(acc[j][t][v]);
     lds_barrier();
     __half* const y = static_cast<__half*>(p.y);
+    constexpr int PIECES = ROWS / 8;   // 16-byte pieces per token
 #pragma unroll 4
-    for (int k = 0; k < 16; ++k) {
-        const int idx = tid + 512 * k, tok = idx >> 5, piece = idx & 31;
+    for (int k = 0; k < 256 * PIECES / 512; ++k) {
+        const int idx = tid + 512 * k, tok = idx / PIECES, piece = idx % PIECES;
         const uint4 v = *reinterpret_cast<const uint4*>(yl + tok * kGemmYLd + piece * 8);
         if (tok0 + tok < p.batch && row0 + piece * 8 < p.out)
             *reinterpret_cast<uint4*>(y + size_t(tok0 + tok) * p.out + row0 + piece * 8) = v;
@@ -207,6 +218,18 @@ hipError_t launch_dense_zero(const LaunchArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
+// Rounds of the chip's 256 compute units, in units of a 256-row round; a 128-row round is priced
+// at 0.75 of one (measured: LDS reads per matrix instruction go up by a third).  128-row tiles
+// are used when they come out cheaper.
+static double rounds_of(int out, int batch, int rows) {
+    const int tiles = ((out + rows - 1) / rows) * ((batch + kGemmTokens - 1) / kGemmTokens);
+    return (rows == 128 ? 0.75 : 1.0) * ((tiles + 255) / 256);
+}
+bool dense_narrow_tiles(int out, int batch) { return rounds_of(out, batch, 128) < rounds_of(out, batch, 256); }
+double dense_rounds(int out, int batch) {
+    return dense_narrow_tiles(out, batch) ? rounds_of(out, batch, 128) : rounds_of(out, batch, 256);
+}
+
 hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {
     KParams p = make_params(a);
     if (a.batch < 1 || p.wdense == nullptr) return hipErrorInvalidValue;
@@ -214,14 +237,22 @@ hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {
         return hipErrorInvalidValue;   // 32-bit byte offsets into x and the dense weight
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<4>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<2>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int ntt = (p.batch + kGemmTokens - 1) / kGemmTokens, nrt = (p.out + kGemmRows - 1) / kGemmRows;
+    const int ntt = (p.batch + kGemmTokens - 1) / kGemmTokens;
+    const bool narrow = dense_narrow_tiles(p.out, p.batch);
+    const int nrt = (p.out + (narrow ? 128 : 256) - 1) / (narrow ? 128 : 256);
     const unsigned wgs = unsigned(8 * ((nrt + 7) / 8) * ntt);
-    hipLaunchKernelGGL(k_gemm, dim3(wgs), dim3(512), kGemmLds, st, p);
+    if (narrow)
+        hipLaunchKernelGGL(k_gemm<2>, dim3(wgs), dim3(512), kGemmLds, st, p);
+    else
+        hipLaunchKernelGGL(k_gemm<4>, dim3(wgs), dim3(512), kGemmLds, st, p);
     return hipGetLastError();
 }
 

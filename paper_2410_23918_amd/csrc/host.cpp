@@ -320,8 +320,7 @@ static int choose_kernel(const Geometry& g, int batch, int n_loaded, size_t work
     int kernel = t_decode <= t_panel ? BITSTACK_KERNEL_DECODE : BITSTACK_KERNEL_PANEL;
     const double t_best = t_decode <= t_panel ? t_decode : t_panel;
     if (n_loaded <= restore_max_blocks() && workspace_bytes >= size_t(g.out) * size_t(g.in) * 2) {
-        const int wgs = ((g.out + 255) / 256) * ((batch + 255) / 256);
-        const double t_mat = 10.0 + double(g.out) * g.in * n_loaded / 6.1e6 + 10.0 + ((wgs + 255) / 256) * 0.035 * g.in;
+        const double t_mat = 10.0 + double(g.out) * g.in * n_loaded / 6.1e6 + 10.0 + dense_rounds(g.out, batch) * 0.035 * g.in;
         if (t_mat < t_best) kernel = BITSTACK_KERNEL_MATERIALISE;
     }
     return kernel;

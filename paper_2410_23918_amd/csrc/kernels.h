@@ -37,6 +37,9 @@ hipError_t launch_panel(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_restore(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_dense_zero(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_dense(const LaunchArgs& a, hipStream_t st);
+// k_gemm's tile choice (128-row tiles or 256-row ones) and its cost in 256-row rounds of the chip
+bool dense_narrow_tiles(int out, int batch);
+double dense_rounds(int out, int batch);
 int restore_max_blocks();
 // decomposition on the device (decompose.hip): W fp32 [out][in], s fp32 [in] (device copy inside the
 // workspace), outputs canonical sign words and fp16 factors on the device

@@ -533,6 +533,28 @@ def test_materialised_path_every_tile_variant(B, out, inn, n):
     assert not y.any()
 
 
+def test_dense_product_with_256_row_tiles(B):
+    """The small shapes above all run the product kernel's 128-row tiles (fewer than 129 of the
+    256-row ones would leave compute units idle).  This shape has 8 x 17 = 136 tiles of 256 rows
+    (one round of the chip) against 272 of 128 rows (two rounds), so it takes the 256-row variant:
+    every output against the oracle, with a ragged last row tile (160 rows) and a ragged last token
+    tile (104 tokens), both output types."""
+    import torch
+    out, inn, n, T = 1952, 256, 2, 4200
+    st = synth_stack(5, out, inn, n)
+    ps = _pack(B, st, max_batch=T)
+    x = acts(5, T, inn)
+    ref = O.forward_dense(st, x, n)
+    wd = torch.empty((out, inn), dtype=torch.float16, device="cuda:0")
+    xd = _to_dev(x)
+    for dt in (torch.float16, torch.float32):
+        y = ps.linear_materialised(xd, n, wd, out_dtype=dt)
+        torch.cuda.synchronize()
+        err = O.relative_error(y.float().cpu().numpy(), ref)
+        print(f"{out}x{inn} materialised B={T} {dt}: {err:.2e}", flush=True)
+        assert err <= TOL
+
+
 def test_library_choice_with_an_optional_scratch_buffer(B):
     """bitstack_linear_batched_ws: same results with and without the scratch buffer; the buffer is
     overwritten exactly when the host-side choice says so, left alone otherwise."""
