@@ -153,7 +153,8 @@ def batch_table(B, torch, dev, n):
             y = torch.empty((b, o), dtype=torch.float16, device=dev)
             us = timed(lambda: ps.linear_batched(x, n, y=y, kernel=B.KERNEL_PANEL), 10 if b <= 64 else 3)
             tf = 2.0 * o * i * b / us / 1e6
-            kern = "k_fused" if b <= 64 else "k_xpack + k_tile"
+            kern = ("k_fused" if b <= 32 else "k_fused or k_xpack + k_tile, the launcher's estimate" if b <= 64
+                    else "k_xpack + k_tile")
             log(f"[bench] batch path {o}x{i} n={n} tokens={b} ({kern}): {us:.1f} us, {tf:.1f} useful TFLOP/s")
             rows.append({"shape": f"{o}x{i}", "tokens": b, "kernel": kern, "us": round(us, 1),
                          "useful_TFLOPs": round(tf, 2)})

@@ -218,16 +218,22 @@ hipError_t launch_dense_zero(const LaunchArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-// Rounds of the chip's 256 compute units, in units of a 256-row round; a 128-row round is priced
-// at 0.75 of one (measured: LDS reads per matrix instruction go up by a third).  128-row tiles
-// are used when they come out cheaper.
-static double rounds_of(int out, int batch, int rows) {
+// Cost model of the product (microseconds, fitted to measurements): a round of workgroups takes
+// in x (a + b x the fraction of the 256 compute units that have a workgroup) - a partly filled
+// chip runs each tile faster (clock, shared caches) - with (a, b) = (0.0196, 0.0148) for 256-row
+// tiles and (0.0111, 0.0089) for 128-row tiles.  The launcher takes the cheaper tile height.
+static double dense_time_us(int out, int in, int batch, int rows) {
     const int tiles = ((out + rows - 1) / rows) * ((batch + kGemmTokens - 1) / kGemmTokens);
-    return (rows == 128 ? 0.75 : 1.0) * ((tiles + 255) / 256);
+    const double a = rows == 128 ? 0.0111 : 0.0196, b = rows == 128 ? 0.0089 : 0.0148;
+    const int full = tiles / 256, rest = tiles % 256;
+    return in * (full * (a + b) + (rest ? a + b * rest / 256.0 : 0.0));
 }
-bool dense_narrow_tiles(int out, int batch) { return rounds_of(out, batch, 128) < rounds_of(out, batch, 256); }
-double dense_rounds(int out, int batch) {
-    return dense_narrow_tiles(out, batch) ? rounds_of(out, batch, 128) : rounds_of(out, batch, 256);
+bool dense_narrow_tiles(int out, int in, int batch) {
+    return dense_time_us(out, in, batch, 128) < dense_time_us(out, in, batch, 256);
+}
+double dense_time_us(int out, int in, int batch) {
+    const double n = dense_time_us(out, in, batch, 128), w = dense_time_us(out, in, batch, 256);
+    return n < w ? n : w;
 }
 
 hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {
@@ -246,7 +252,7 @@ hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {
         attr_set = true;
     }
     const int ntt = (p.batch + kGemmTokens - 1) / kGemmTokens;
-    const bool narrow = dense_narrow_tiles(p.out, p.batch);
+    const bool narrow = dense_narrow_tiles(p.out, p.in, p.batch);
     const int nrt = (p.out + (narrow ? 128 : 256) - 1) / (narrow ? 128 : 256);
     const unsigned wgs = unsigned(8 * ((nrt + 7) / 8) * ntt);
     if (narrow)

@@ -302,25 +302,23 @@ int bitstack_weight_shape(const bitstack_weight_t* w, int* out, int* in, int* k,
 // measured on MI355X; decode: ~2.4 GB/ms of block stream plus ~15 us per launch.
 static int choose_kernel(const Geometry& g, int batch, int n_loaded, size_t workspace_bytes) {
     if (batch == 1) return BITSTACK_KERNEL_DECODE;
-    const double blk_bytes = double(g.block_stride);
-    const double t_decode = batch * (15.0 + n_loaded * blk_bytes / 2.4e6);
-    const int row_tiles = (g.out + 63) / 64;
-    const int chunk_pairs = (g.in / 256 + 1) / 2;
+    // the decode kernel once per token: ~13 us + the block stream at ~4.3 TB/s (measured)
+    const double t_decode = batch * (13.0 + n_loaded * double(g.block_stride) / 4.3e6);
     double t_panel;
-    if (batch <= 64) {
-        const int split = small_batch_split(g.out, g.in, batch, g.part_slots);
-        const int wgs = row_tiles * ((batch + 31) / 32) * split;
-        t_panel = ((wgs + 255) / 256) * (15.0 + 1.0 * n_loaded * ((chunk_pairs + split - 1) / split)) + (split > 1 ? 5.0 : 0.0);
+    if (batch <= kSmallBatch) {
+        t_panel = fused_time_us(g.out, g.in, batch, n_loaded, g.part_slots);
+        if (batch > 32 && g.xpack_bytes) {   // launch_panel takes the cheaper of the two here
+            const double t_tile = tile_time_us(g.out, g.in, batch, n_loaded);
+            t_panel = t_tile < t_panel ? t_tile : t_panel;
+        }
     } else {
-        // up to 256 tokens only one wavefront per SIMD has tokens to multiply: half the product time
-        const int wgs = row_tiles * ((batch + 511) / 512);
-        const double rounds = wgs <= 256 ? 1.0 : wgs / 256.0;   // later workgroups start as earlier ones end
-        t_panel = rounds * (15.0 + chunk_pairs * (1.0 * n_loaded + (batch > 256 ? 13.0 : 6.5)));
+        t_panel = tile_time_us(g.out, g.in, batch, n_loaded);
     }
     int kernel = t_decode <= t_panel ? BITSTACK_KERNEL_DECODE : BITSTACK_KERNEL_PANEL;
     const double t_best = t_decode <= t_panel ? t_decode : t_panel;
     if (n_loaded <= restore_max_blocks() && workspace_bytes >= size_t(g.out) * size_t(g.in) * 2) {
-        const double t_mat = 10.0 + double(g.out) * g.in * n_loaded / 6.1e6 + 10.0 + dense_rounds(g.out, batch) * 0.035 * g.in;
+        // restore (~6.1 T weight-element-blocks/s) + product, ~10 us fixed each
+        const double t_mat = 10.0 + double(g.out) * g.in * n_loaded / 6.1e6 + 10.0 + dense_time_us(g.out, g.in, batch);
         if (t_mat < t_best) kernel = BITSTACK_KERNEL_MATERIALISE;
     }
     return kernel;

@@ -37,9 +37,13 @@ hipError_t launch_panel(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_restore(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_dense_zero(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_dense(const LaunchArgs& a, hipStream_t st);
-// k_gemm's tile choice (128-row tiles or 256-row ones) and its cost in 256-row rounds of the chip
-bool dense_narrow_tiles(int out, int batch);
-double dense_rounds(int out, int batch);
+// k_gemm's tile choice (128-row tiles or 256-row ones) and its estimated duration
+bool dense_narrow_tiles(int out, int in, int batch);
+double dense_time_us(int out, int in, int batch);
+// estimated durations of the two batch kernels (microseconds); launch_panel takes the cheaper one
+// for 33..64 tokens
+double fused_time_us(int out, int in, int batch, int n_loaded, int part_slots);
+double tile_time_us(int out, int in, int batch, int n_loaded);
 int restore_max_blocks();
 // decomposition on the device (decompose.hip): W fp32 [out][in], s fp32 [in] (device copy inside the
 // workspace), outputs canonical sign words and fp16 factors on the device

@@ -961,9 +961,34 @@ hipError_t launch_restore(const LaunchArgs& a, hipStream_t st) {
 }
 int restore_max_blocks() { return kTileMaxBlocks; }
 
+// Estimated durations (microseconds, constants fitted to measurements).  k_fused: per round of
+// 256 workgroups ~10 us fixed + ~0.93 us per block and pair of column chunks of a workgroup; later
+// workgroups start as earlier ones end, so rounds beyond the first count fractionally.
+double fused_time_us(int out, int in, int batch, int n_loaded, int part_slots) {
+    const int row_tiles = (out + 2 * kTileRows - 1) / (2 * kTileRows), chunk_pairs = (in / kChunkCols + 1) / 2;
+    const int split = small_batch_split(out, in, batch, part_slots);
+    const int wgs = row_tiles * ((batch + 31) / 32) * split;
+    const double rounds = wgs <= 256 ? 1.0 : wgs / 256.0;
+    return rounds * (10.0 + 0.93 * n_loaded * ((chunk_pairs + split - 1) / split)) + (split > 1 ? 5.0 : 0.0);
+}
+// k_tile: per pair of column chunks ~1.0 us per block for the rebuild + 13 us for the product
+// (6.5 us up to 256 tokens, where only one wavefront per SIMD has tokens to multiply); 15 % less
+// of both when the chip is not full.
+double tile_time_us(int out, int in, int batch, int n_loaded) {
+    const int row_tiles = (out + 2 * kTileRows - 1) / (2 * kTileRows), chunk_pairs = (in / kChunkCols + 1) / 2;
+    const int wgs = row_tiles * ((batch + kTileTokens - 1) / kTileTokens);
+    const double rounds = wgs <= 256 ? 1.0 : wgs / 256.0, scale = wgs <= 256 ? 0.85 : 1.0;
+    return rounds * (15.0 + chunk_pairs * scale * (1.0 * n_loaded + (batch > 256 ? 13.0 : 6.5)));
+}
+
 hipError_t launch_panel(const LaunchArgs& a, hipStream_t st) {
     KParams p = make_params(a);
     if (a.n_loaded < 1 || a.batch < 1) return hipErrorInvalidValue;
+    // 33..64 tokens: k_fused rebuilds the signed tiles twice; with many row tiles the weight-tile
+    // kernel, which rebuilds once, is the cheaper one
+    if (a.batch > 32 && a.batch <= kFusedMaxBatch && fused_fits(p) && tile_fits(p) &&
+        tile_time_us(p.out, p.in, p.batch, p.n_loaded) < fused_time_us(p.out, p.in, p.batch, p.n_loaded, p.part_slots))
+        return launch_tile(p, st);
     if (a.batch <= kFusedMaxBatch && fused_fits(p)) return launch_fused(p, st);
     if (a.batch > kFusedMaxBatch && tile_fits(p)) return launch_tile(p, st);
     if (a.batch > 256) return launch_panel_t<4>(p, st);

@@ -533,6 +533,27 @@ def test_materialised_path_every_tile_variant(B, out, inn, n):
     assert not y.any()
 
 
+def test_weight_tile_kernel_takes_33_to_64_tokens_when_row_tiles_are_many(B):
+    """For 33..64 tokens the batch launcher takes the weight-tile kernel instead of the small-batch
+    one when that is estimated cheaper: here 224 row tiles, where the small-batch kernel would need
+    448 workgroups and rebuild every signed tile twice.  Every output against the oracle, on both
+    sides of the 32-token groups, both output types."""
+    import torch
+    out, inn, n = 14336, 512, 3
+    st = synth_stack(3, out, inn, n, tag=6)
+    ps = _pack(B, st, max_batch=128)
+    x = acts(3, 64, inn, tag=6)
+    ref = O.forward_dense(st, x, n)
+    for b in (33, 48, 64):
+        assert B.choose_kernel(out, inn, n, 128, b, n, 0) == B.KERNEL_PANEL
+        for dt in (torch.float16, torch.float32):
+            y = ps.linear_batched(_to_dev(x[:b]), n, out_dtype=dt, kernel=B.KERNEL_PANEL)
+            torch.cuda.synchronize()
+            err = O.relative_error(y.float().cpu().numpy(), ref[:b])
+            print(f"{out}x{inn} B={b} {dt}: {err:.2e}", flush=True)
+            assert err <= TOL
+
+
 def test_dense_product_with_256_row_tiles(B):
     """The small shapes above all run the product kernel's 128-row tiles (fewer than 129 of the
     256-row ones would leave compute units idle).  This shape has 8 x 17 = 136 tiles of 256 rows
