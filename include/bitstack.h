@@ -68,7 +68,7 @@ enum { BITSTACK_Y_F16 = 0, BITSTACK_Y_F32 = 1 };
 enum {
     BITSTACK_KERNEL_AUTO      = 0,
     BITSTACK_KERNEL_REFERENCE = 1, /* plain vector-ALU kernel, any batch <= max_batch            */
-    BITSTACK_KERNEL_DECODE    = 2, /* matrix-core sign-stream kernel, one launch per token       */
+    BITSTACK_KERNEL_DECODE    = 2, /* matrix-core sign-stream kernel, up to 4 tokens per launch  */
     BITSTACK_KERNEL_PANEL     = 3, /* batch kernels: weight rebuilt on chip (Eq. 8) and multiplied
                                       with the activations on the matrix cores, any batch        */
     BITSTACK_KERNEL_MATERIALISE = 4 /* restore the weight to a dense scratch, then a dense product;

@@ -302,8 +302,7 @@ int bitstack_weight_shape(const bitstack_weight_t* w, int* out, int* in, int* k,
 // measured on MI355X; decode: ~2.4 GB/ms of block stream plus ~15 us per launch.
 static int choose_kernel(const Geometry& g, int batch, int n_loaded, size_t workspace_bytes) {
     if (batch == 1) return BITSTACK_KERNEL_DECODE;
-    // the decode kernel once per token: ~13 us + the block stream at ~4.3 TB/s (measured)
-    const double t_decode = batch * (13.0 + n_loaded * double(g.block_stride) / 4.3e6);
+    const double t_decode = decode_tokens_time_us(g, batch, n_loaded);   // up to four tokens per launch
     double t_panel;
     if (batch <= kSmallBatch) {
         t_panel = fused_time_us(g.out, g.in, batch, n_loaded, g.part_slots);
@@ -358,18 +357,9 @@ static int linear_impl(const void* x, int batch, const bitstack_weight_t* w, int
             case BITSTACK_KERNEL_REFERENCE:
                 e = launch_reference(a, st);
                 break;
-            case BITSTACK_KERNEL_DECODE: {
-                // one launch per token: the decode kernel handles a single activation vector
-                const size_t ybytes = size_t(g.out) * (a.y_f32 ? 4 : 2);
-                LaunchArgs t = a;
-                t.batch = 1;
-                for (int b = 0; b < batch && e == hipSuccess; ++b) {
-                    t.x = static_cast<const unsigned char*>(x) + size_t(b) * g.in * 2;
-                    t.y = static_cast<unsigned char*>(y) + size_t(b) * ybytes;
-                    e = launch_decode(t, st);
-                }
+            case BITSTACK_KERNEL_DECODE:
+                e = launch_decode_tokens(a, st);   // the decode kernel takes single activation vectors
                 break;
-            }
             case BITSTACK_KERNEL_PANEL:
                 e = launch_panel(a, st);
                 break;

@@ -32,6 +32,9 @@ hipError_t launch_reference(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_decode(const LaunchArgs& a, hipStream_t st);
 // up to 4 batch-1 calls in one launch; all must use the same column slab (Geometry::min_slab)
 hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st);
+// a.batch tokens through the decode kernel, up to four per launch
+hipError_t launch_decode_tokens(const LaunchArgs& a, hipStream_t st);
+double decode_tokens_time_us(const Geometry& g, int batch, int n_loaded);
 hipError_t launch_panel(const LaunchArgs& a, hipStream_t st);
 // materialising path: W' diag(1/s) of the loaded prefix -> a.wdense; then y = x wdense^T
 hipError_t launch_restore(const LaunchArgs& a, hipStream_t st);

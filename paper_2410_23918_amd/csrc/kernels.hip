@@ -754,14 +754,21 @@ static hipError_t launch_decode_t(KGroup& grp, int bg_req, hipStream_t st) {
         }
         for (int t = int((work + 255) / 256); t <= tallest; ++t) {
             long wgs = 0;
-            for (int i = 0; i < grp.count; ++i)
+            bool workspace_ok = true;   // members sharing a stack share its partial-row slots
+            for (int i = 0; i < grp.count; ++i) {
                 wgs += long(grp.s[i].n_rs) * grp.s[i].n_ks * ((grp.s[i].n_loaded + t - 1) / t);
+                int slots = 0;
+                for (int j = 0; j < grp.count; ++j)
+                    if (grp.s[j].blocks == grp.s[i].blocks) slots += grp.s[j].n_ks * ((grp.s[j].n_loaded + t - 1) / t);
+                workspace_ok = workspace_ok && slots <= grp.s[i].part_slots;
+            }
             blocks_per_wg = t;
-            if (wgs <= 256) break;
+            if (wgs <= 256 && workspace_ok) break;
         }
         if (blocks_per_wg < 1) blocks_per_wg = 1;
     }
     unsigned next = 0;
+    int part_shift[kMaxGroup] = {}, ctr_shift[kMaxGroup] = {};
     for (int i = 0; i < grp.count; ++i) {
         KParams& p = grp.s[i];
         int bg = bg_req;
@@ -782,9 +789,26 @@ static hipError_t launch_decode_t(KGroup& grp, int bg_req, hipStream_t st) {
         if (bg > p.n_loaded) bg = p.n_loaded;
         while ((p.n_loaded + bg - 1) / bg > kMaxBlocksPerWg) ++bg;
         p.n_bg = bg;
-        if (p.n_rs > kCounterSlots || p.n_ks * bg > p.part_slots) return hipErrorInvalidValue;
+        // Members that share a stack (several tokens of a small batch in one launch) share its
+        // split-accumulation workspace: each gets its own partial rows and arrival counters
+        // behind those of the members before it.
+        int slots_before = 0, ctrs_before = 0;
+        for (int j = 0; j < i; ++j)
+            if (grp.s[j].blocks == p.blocks) {
+                slots_before += grp.s[j].n_ks * grp.s[j].n_bg;
+                ctrs_before += grp.s[j].n_rs;
+            }
+        if (ctrs_before + p.n_rs > kCounterSlots || slots_before + p.n_ks * bg > p.part_slots)
+            return hipErrorInvalidValue;   // nothing has been launched
+        part_shift[i] = slots_before;
+        ctr_shift[i] = ctrs_before;
         grp.base[i] = next;
         next += (unsigned(p.n_rs * p.n_ks) * unsigned(bg) + 7u) & ~7u;
+    }
+    for (int i = 0; i < grp.count; ++i) {   // (after the loop above, which compares the unshifted pointers)
+        grp.s[i].part += size_t(part_shift[i]) * grp.s[i].out;
+        grp.s[i].part_slots -= part_shift[i];
+        grp.s[i].ctr += ctr_shift[i];
     }
     for (int i = grp.count; i <= kMaxGroup; ++i) grp.base[i] = next;
     const size_t smem = size_t(KS) * 68 + 2 * size_t(kDecodeRows) * 32 + size_t(kProducers) * kMaxBlocksPerWg * 4 +
@@ -824,5 +848,67 @@ hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st) {
 }
 
 hipError_t launch_decode(const LaunchArgs& a, hipStream_t st) { return launch_decode_group(&a, 1, st); }
+
+// Estimated duration (microseconds) of launch_decode_tokens: per launch ~13 us + the blocks a
+// workgroup walks through at ~7.3 us per 1024 x 1024 signs, with the same rule for the number of
+// blocks per workgroup as the launcher (one round of 256 workgroups, the shared workspace).
+double decode_tokens_time_us(const Geometry& g, int batch, int n_loaded) {
+    const int ks = g.min_slab;
+    const int n_rs = (g.out + kDecodeRows - 1) / kDecodeRows, n_ks = g.in / ks, pairs = n_rs * n_ks;
+    const double t_block = 7.3 * ks / 1024.0;
+    // blocks per workgroup of a launch with m tokens of this stack; 0: the launcher refuses
+    auto plan = [&](int m) -> double {
+        if (m == 1) {
+            int bg = 256 / pairs;
+            bg = bg < 1 ? 1 : bg > n_loaded ? n_loaded : bg;
+            return double((n_loaded + bg - 1) / bg) * ((pairs * bg + 255) / 256);
+        }
+        for (int c = (m * pairs * n_loaded + 255) / 256; c <= n_loaded; ++c) {
+            const int bg = (n_loaded + c - 1) / c;
+            if (m * pairs * bg <= 256 && m * n_ks * bg <= g.part_slots) return c;
+        }
+        if (m * n_ks <= g.part_slots) return double(n_loaded) * ((m * pairs + 255) / 256);   // several rounds
+        return 0.0;
+    };
+    double total = 0.0;
+    int per_launch = kMaxGroup;
+    for (int b = 0; b < batch;) {
+        const int m = batch - b < per_launch ? batch - b : per_launch;
+        const double t = plan(m);
+        if (t == 0.0) {
+            per_launch = m / 2;
+            continue;
+        }
+        total += 13.0 + t * t_block;
+        b += m;
+    }
+    return total;
+}
+
+// A small batch through the decode kernel: up to four tokens per launch, each a member of the
+// group with its own x row, y row and share of the stack's workspace; fewer per launch when the
+// workspace is too small for that many.
+hipError_t launch_decode_tokens(const LaunchArgs& a, hipStream_t st) {
+    const size_t xbytes = size_t(a.geo.in) * 2, ybytes = size_t(a.geo.out) * (a.y_f32 ? 4 : 2);
+    int per_launch = kMaxGroup;
+    for (int b = 0; b < a.batch;) {
+        const int count = a.batch - b < per_launch ? a.batch - b : per_launch;
+        LaunchArgs t[kMaxGroup];
+        for (int i = 0; i < count; ++i) {
+            t[i] = a;
+            t[i].batch = 1;
+            t[i].x = static_cast<const unsigned char*>(a.x) + size_t(b + i) * xbytes;
+            t[i].y = static_cast<unsigned char*>(a.y) + size_t(b + i) * ybytes;
+        }
+        const hipError_t e = launch_decode_group(t, count, st);
+        if (e == hipErrorInvalidValue && count > 1) {   // refused before any launch: workspace too small
+            per_launch = count / 2;
+            continue;
+        }
+        if (e != hipSuccess) return e;
+        b += count;
+    }
+    return hipSuccess;
+}
 
 }  // namespace bitstack

@@ -268,6 +268,29 @@ def test_job_list_merging_rules(B):
         assert torch.equal(got[k], want), k
 
 
+@pytest.mark.parametrize("out,inn,n_slots", [(1056, 2048, 6), (4096, 4096, 16), (2048, 1024, 2)])
+def test_small_batch_through_the_decode_kernel(B, out, inn, n_slots):
+    """Batches of 2..9 tokens through the decode kernel: up to four tokens share a launch, each
+    with its own activation row, output row and piece of the stack's split-accumulation workspace
+    (the third shape has a workspace too small for four, so the launcher falls back to fewer per
+    launch).  Every token against the oracle; a second pass over the same buffers checks that the
+    arrival counters were left at zero; the single-token result is unchanged afterwards."""
+    st = synth_stack(3, out, inn, n_slots, tag=9)
+    ps = _pack(B, st, max_batch=16)
+    x = acts(3, 9, inn, tag=9)
+    for nl in sorted({1, n_slots // 2, n_slots} - {0}):
+        ref = O.forward_dense(st, x, nl)
+        for b in (2, 3, 4, 5, 9):
+            for rep in range(2):
+                y = _run(B, ps, x[:b], nl, B.KERNEL_DECODE, "f32" if rep else "f16")
+                assert y.shape == (b, out)
+                err = O.relative_error(y, ref[:b])
+                print(f"{out}x{inn} n_loaded={nl} B={b} pass {rep}: {err:.2e}", flush=True)
+                assert err <= TOL
+        y1 = _run(B, ps, x[:1], nl, B.KERNEL_DECODE)
+        assert O.relative_error(y1, ref[:1]) <= TOL
+
+
 def test_degenerate_activations(B):
     """x = 0 gives y = 0 exactly (the panel's quantisation scale is zero: nothing may divide by
     it); a one-hot x picks one column of W' diag(1/s); a huge and a tiny x keep the relative error
