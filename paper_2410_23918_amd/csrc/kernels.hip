@@ -27,6 +27,8 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
+#include <vector>
+
 #include <type_traits>
 
 #include "kernels.h"
@@ -849,50 +851,71 @@ hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st) {
 
 hipError_t launch_decode(const LaunchArgs& a, hipStream_t st) { return launch_decode_group(&a, 1, st); }
 
-// Estimated duration (microseconds) of launch_decode_tokens: per launch ~13 us + the blocks a
-// workgroup walks through at ~7.3 us per 1024 x 1024 signs, with the same rule for the number of
-// blocks per workgroup as the launcher (one round of 256 workgroups, the shared workspace).
-double decode_tokens_time_us(const Geometry& g, int batch, int n_loaded) {
+// Estimated duration (microseconds) of one decode launch with m tokens of one stack: ~13 us +
+// the blocks a workgroup walks through at ~7.3 us per 1024 x 1024 signs, with the launcher's own
+// rule for the number of blocks per workgroup (one round of 256 workgroups, the shared
+// workspace).  0: the launcher would refuse (workspace too small for m tokens).
+static double decode_launch_time_us(const Geometry& g, int m, int n_loaded) {
     const int ks = g.min_slab;
     const int n_rs = (g.out + kDecodeRows - 1) / kDecodeRows, n_ks = g.in / ks, pairs = n_rs * n_ks;
-    const double t_block = 7.3 * ks / 1024.0;
-    // blocks per workgroup of a launch with m tokens of this stack; 0: the launcher refuses
-    auto plan = [&](int m) -> double {
-        if (m == 1) {
-            int bg = 256 / pairs;
-            bg = bg < 1 ? 1 : bg > n_loaded ? n_loaded : bg;
-            return double((n_loaded + bg - 1) / bg) * ((pairs * bg + 255) / 256);
-        }
-        for (int c = (m * pairs * n_loaded + 255) / 256; c <= n_loaded; ++c) {
+    double blocks = 0.0;   // per workgroup, times rounds
+    if (m == 1) {
+        int bg = 256 / pairs;
+        bg = bg < 1 ? 1 : bg > n_loaded ? n_loaded : bg;
+        blocks = double((n_loaded + bg - 1) / bg) * ((pairs * bg + 255) / 256);
+    } else {
+        for (int c = (m * pairs * n_loaded + 255) / 256; c <= n_loaded && blocks == 0.0; ++c) {
             const int bg = (n_loaded + c - 1) / c;
-            if (m * pairs * bg <= 256 && m * n_ks * bg <= g.part_slots) return c;
+            if (m * pairs * bg <= 256 && m * n_ks * bg <= g.part_slots) blocks = c;
         }
-        if (m * n_ks <= g.part_slots) return double(n_loaded) * ((m * pairs + 255) / 256);   // several rounds
-        return 0.0;
-    };
-    double total = 0.0;
-    int per_launch = kMaxGroup;
-    for (int b = 0; b < batch;) {
-        const int m = batch - b < per_launch ? batch - b : per_launch;
-        const double t = plan(m);
-        if (t == 0.0) {
-            per_launch = m / 2;
-            continue;
-        }
-        total += 13.0 + t * t_block;
-        b += m;
+        if (blocks == 0.0 && m * n_ks <= g.part_slots) blocks = double(n_loaded) * ((m * pairs + 255) / 256);
+        if (blocks == 0.0) return 0.0;
     }
-    return total;
+    return 13.0 + blocks * 7.3 * ks / 1024.0;
 }
 
-// A small batch through the decode kernel: up to four tokens per launch, each a member of the
-// group with its own x row, y row and share of the stack's workspace; fewer per launch when the
-// workspace is too small for that many.
+// How a small batch is cut into launches of one to four tokens: the cut with the smallest
+// estimated total (three tokens of a tall stack are cheaper as 2 + 1 than as one launch whose
+// workgroups each walk the whole stack).  sizes[] receives the launch sizes in order; returns
+// the estimate.
+static double plan_decode_tokens(const Geometry& g, int batch, int n_loaded, int* sizes, int* n_launches) {
+    double t_of[kMaxGroup + 1] = {};
+    for (int m = 1; m <= kMaxGroup; ++m) t_of[m] = decode_launch_time_us(g, m, n_loaded);
+    // best[b]: cheapest way to run b tokens; take[b]: size of its last launch
+    std::vector<double> best(size_t(batch) + 1, 0.0);
+    std::vector<int> take(size_t(batch) + 1, 1);
+    for (int b = 1; b <= batch; ++b) {
+        best[b] = -1.0;
+        for (int m = 1; m <= kMaxGroup && m <= b; ++m) {
+            if (t_of[m] == 0.0) continue;
+            const double t = best[b - m] + t_of[m];
+            if (best[b] < 0.0 || t < best[b]) {
+                best[b] = t;
+                take[b] = m;
+            }
+        }
+    }
+    int n = 0;
+    for (int b = batch; b > 0; b -= take[b])
+        if (sizes) sizes[n++] = take[b];
+    if (n_launches) *n_launches = n;
+    return best[batch];
+}
+
+double decode_tokens_time_us(const Geometry& g, int batch, int n_loaded) {
+    return plan_decode_tokens(g, batch, n_loaded, nullptr, nullptr);
+}
+
+// A small batch through the decode kernel: one to four tokens per launch, each a member of the
+// group with its own x row, y row and share of the stack's workspace.
 hipError_t launch_decode_tokens(const LaunchArgs& a, hipStream_t st) {
     const size_t xbytes = size_t(a.geo.in) * 2, ybytes = size_t(a.geo.out) * (a.y_f32 ? 4 : 2);
-    int per_launch = kMaxGroup;
-    for (int b = 0; b < a.batch;) {
-        const int count = a.batch - b < per_launch ? a.batch - b : per_launch;
+    std::vector<int> sizes(size_t(a.batch));
+    int n_launches = 0;
+    plan_decode_tokens(a.geo, a.batch, a.n_loaded, sizes.data(), &n_launches);
+    int b = 0;
+    for (int l = 0; l < n_launches; ++l) {
+        const int count = sizes[l];
         LaunchArgs t[kMaxGroup];
         for (int i = 0; i < count; ++i) {
             t[i] = a;
@@ -900,10 +923,11 @@ hipError_t launch_decode_tokens(const LaunchArgs& a, hipStream_t st) {
             t[i].x = static_cast<const unsigned char*>(a.x) + size_t(b + i) * xbytes;
             t[i].y = static_cast<unsigned char*>(a.y) + size_t(b + i) * ybytes;
         }
-        const hipError_t e = launch_decode_group(t, count, st);
-        if (e == hipErrorInvalidValue && count > 1) {   // refused before any launch: workspace too small
-            per_launch = count / 2;
-            continue;
+        hipError_t e = launch_decode_group(t, count, st);
+        if (e == hipErrorInvalidValue && count > 1) {
+            // refused before anything was launched (e.g. a forced tuning the plan does not know): one by one
+            e = hipSuccess;
+            for (int i = 0; i < count && e == hipSuccess; ++i) e = launch_decode_group(t + i, 1, st);
         }
         if (e != hipSuccess) return e;
         b += count;
