@@ -292,14 +292,11 @@ int bitstack_weight_shape(const bitstack_weight_t* w, int* out, int* in, int* k,
     return BITSTACK_OK;
 }
 
-// Which kernel serves (batch, n_loaded) fastest.  Per-token decode launches stream the blocks
-// once per token.  The batch path has two kernels: up to 64 tokens, signed tiles are rebuilt per
-// group of 32 tokens; beyond that a weight tile is rebuilt once per 512 tokens and multiplied
-// with them.  Both take ~1 us per block and pair of 256-column chunks of a 64-row tile, the
-// second another ~13 us per chunk pair for the product.  With a scratch buffer for the dense
-// weight, restoring it once (~6.1e6 weight elements x blocks per us) and one dense product
-// (256 x 256 tiles, ~0.035 us per input column each) wins for prefill-sized batches.  Rates
-// measured on MI355X; decode: ~2.4 GB/ms of block stream plus ~15 us per launch.
+// Which kernel serves (batch, n_loaded) fastest, from estimates that live beside the launchers
+// (constants fitted to measurements on MI355X): the decode kernel with up to four tokens per
+// launch streams the blocks once per token; the batch path rebuilds signed tiles per group of 32
+// tokens (up to 64 tokens) or a weight tile once per 512 tokens; with a scratch buffer for the
+// dense weight, restoring it once and one dense product wins for prefill-sized batches.
 static int choose_kernel(const Geometry& g, int batch, int n_loaded, size_t workspace_bytes) {
     if (batch == 1) return BITSTACK_KERNEL_DECODE;
     const double t_decode = decode_tokens_time_us(g, batch, n_loaded);   // up to four tokens per launch
