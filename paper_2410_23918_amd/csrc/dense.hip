@@ -222,17 +222,17 @@ hipError_t launch_dense_zero(const LaunchArgs& a, hipStream_t st) {
 // in x (a + b x the fraction of the 256 compute units that have a workgroup) - a partly filled
 // chip runs each tile faster (clock, shared caches) - with (a, b) = (0.0196, 0.0148) for 256-row
 // tiles and (0.0111, 0.0089) for 128-row tiles.  The launcher takes the cheaper tile height.
-static double dense_time_us(int out, int in, int batch, int rows) {
+static double tile_rounds_time_us(int out, int in, int batch, int rows) {
     const int tiles = ((out + rows - 1) / rows) * ((batch + kGemmTokens - 1) / kGemmTokens);
     const double a = rows == 128 ? 0.0111 : 0.0196, b = rows == 128 ? 0.0089 : 0.0148;
     const int full = tiles / 256, rest = tiles % 256;
     return in * (full * (a + b) + (rest ? a + b * rest / 256.0 : 0.0));
 }
 bool dense_narrow_tiles(int out, int in, int batch) {
-    return dense_time_us(out, in, batch, 128) < dense_time_us(out, in, batch, 256);
+    return tile_rounds_time_us(out, in, batch, 128) < tile_rounds_time_us(out, in, batch, 256);
 }
 double dense_time_us(int out, int in, int batch) {
-    const double n = dense_time_us(out, in, batch, 128), w = dense_time_us(out, in, batch, 256);
+    const double n = tile_rounds_time_us(out, in, batch, 128), w = tile_rounds_time_us(out, in, batch, 256);
     return n < w ? n : w;
 }
 
