@@ -150,6 +150,17 @@ def test_kernel_choice_is_host_logic():
     assert B.choose_kernel(14336, 4096, 16, 16, 16, 16, big) == B.KERNEL_PANEL      # too few tokens to pay for restoring
     assert B.choose_kernel(4096, 4096, 16, 64, 2, 2, big) in (B.KERNEL_DECODE, B.KERNEL_PANEL)
     assert B.choose_kernel(4096, 4096, 16, 64, 2, 0) == B.KERNEL_AUTO
+    # where the measured crossovers lie (Llama-3-8B shapes, 16 blocks): two tokens share a decode
+    # launch, eight go to the batch kernels; with a scratch buffer the 4096-row shapes take the
+    # materialising path from ~65 tokens on (128-row product tiles fill the chip), the 14336-row
+    # shape only from ~700
+    assert B.choose_kernel(14336, 4096, 16, 2048, 2, 16, 0) == B.KERNEL_DECODE
+    assert B.choose_kernel(14336, 4096, 16, 2048, 8, 16, 0) == B.KERNEL_PANEL
+    assert B.choose_kernel(4096, 4096, 16, 2048, 128, 16, big) == B.KERNEL_MATERIALISE
+    assert B.choose_kernel(4096, 14336, 16, 2048, 128, 16, big) == B.KERNEL_MATERIALISE
+    assert B.choose_kernel(14336, 4096, 16, 2048, 128, 16, big) == B.KERNEL_PANEL
+    assert B.choose_kernel(14336, 4096, 16, 2048, 512, 16, big) == B.KERNEL_PANEL
+    assert B.choose_kernel(14336, 4096, 16, 2048, 1024, 16, big) == B.KERNEL_MATERIALISE
     L = B.lib()
     assert L.bitstack_choose_kernel(4096, 100, 16, 1, 1, 1, 0) == -2
     assert L.bitstack_choose_kernel(4096, 4096, 16, 8, 9, 1, 0) == -3
