@@ -275,23 +275,6 @@ int bitstack_decompose(const float* W, const float* s, int out, int in, int k, i
                        uint32_t* sign_words, uint16_t* U, uint16_t* V, void* workspace,
                        size_t workspace_bytes, bitstack_stream_t stream);
 
-/* Tuning hooks for benchmarks (process-wide, not thread-safe).  value 0 restores
- * the built-in choice.  Unknown options or unsupported values give BITSTACK_E_ARG
- * (at the next launch for values). */
-enum {
-    BITSTACK_OPT_DECODE_KSLAB = 2, /* input columns per workgroup of the decode kernel: 256, 512, 1024 */
-    BITSTACK_OPT_DECODE_BGROUPS = 3 /* workgroups sharing one (row slab, column slab) pair; each
-                                       walks every BGROUPS-th block of the loaded prefix      */
-};
-int bitstack_set_option(int option, int value);
-
-/* Measurement aid: reads device_buf[0, bytes) once with 128-bit loads (nothing is
- * written unless the xor of the data hits one magic value).  Gives the achievable
- * HBM read rate that the sign stream of the decode path is compared with.
- * device_buf 16-byte aligned, bytes % 16 == 0, device_sink >= 4 bytes. */
-int bitstack_probe_read(const void* device_buf, size_t bytes, void* device_sink, int workgroups,
-                        bitstack_stream_t stream);
-
 /* Shape queries on a handle. */
 int bitstack_weight_shape(const bitstack_weight_t* w, int* out, int* in, int* k, int* n,
                           int* max_batch);

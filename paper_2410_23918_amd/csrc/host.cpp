@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "../../include/bitstack.h"
+#include "../../include/bitstack_bench.h"
 #include "kernels.h"
 #include "kparams.h"
 #include "layout.h"
@@ -508,8 +509,12 @@ int bitstack_probe_read(const void* device_buf, size_t bytes, void* device_sink,
 int bitstack_set_option(int option, int value) {
     if (value < 0) return BITSTACK_E_ARG;
     switch (option) {
-        case BITSTACK_OPT_DECODE_KSLAB: decode_tuning().kslab = value; return BITSTACK_OK;
+        case BITSTACK_OPT_DECODE_LEGACY_KSLAB: decode_tuning().legacy_kslab = value; return BITSTACK_OK;
         case BITSTACK_OPT_DECODE_BGROUPS: decode_tuning().bgroups = value; return BITSTACK_OK;
+        case BITSTACK_OPT_DECODE_TILES: decode_tuning().tiles = value; return BITSTACK_OK;
+        case BITSTACK_OPT_DECODE_KS_CHUNKS: decode_tuning().ks_chunks = value; return BITSTACK_OK;
+        case BITSTACK_OPT_DECODE_EARLY: decode_tuning().early = value - 1; return BITSTACK_OK;
+        case BITSTACK_OPT_DECODE_LEGACY: decode_tuning().legacy = value; return BITSTACK_OK;
         default: return BITSTACK_E_ARG;
     }
 }

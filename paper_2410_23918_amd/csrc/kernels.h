@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "layout.h"
 
 namespace bitstack {
@@ -19,19 +21,28 @@ struct LaunchArgs {
     void* wdense = nullptr;  // device fp16 [out][in]: the restored weight of the materialising path
 };
 
-// Tunables of the decode kernel (0 = choose by shape).
+// Limits of the decode kernel's work split
+constexpr int kDecodeMaxRangeChunks = 32;   // 256-column chunks per workgroup (x/s table in LDS)
+constexpr int kDecodeMaxBlocksPerWg = 32;   // blocks a workgroup walks through
+
+// Tunables of the decode kernel (0 = choose by shape); measurement hooks, set through the
+// bench-only entry point.  Atomics: a call may read them while another thread sets them.
 struct DecodeTuning {
-    int kslab;   // columns per workgroup: 256, 512 or 1024
-    int bgroups; // block groups (workgroups per row/column slab pair)
+    std::atomic<int> tiles{0};      // 32-row tiles per wavefront: 2 or 4 (512 or 1024 rows per workgroup)
+    std::atomic<int> ks_chunks{0};  // 256-column chunks per workgroup
+    std::atomic<int> bgroups{0};    // block groups (workgroups per row slab / column range pair)
+    std::atomic<int> early{-1};     // chunks of the first sign window requested before the prologue's arithmetic
+    std::atomic<int> legacy{0};     // 1: the producer/consumer kernel (kernels.hip) instead of decode.hip
+    std::atomic<int> legacy_kslab{0};
 };
 DecodeTuning& decode_tuning();
 
 hipError_t launch_stream_read(const void* buf, size_t bytes, void* sink, int blocks, hipStream_t st);
 hipError_t launch_zero(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_reference(const LaunchArgs& a, hipStream_t st);
-hipError_t launch_decode(const LaunchArgs& a, hipStream_t st);
-// up to 4 batch-1 calls in one launch; all must use the same column slab (Geometry::min_slab)
+// up to 4 batch-1 calls that read the same activation vector in one launch
 hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st);
+hipError_t launch_decode_group_old(const LaunchArgs* a, int count, hipStream_t st);
 // a.batch tokens through the decode kernel, up to four per launch
 hipError_t launch_decode_tokens(const LaunchArgs& a, hipStream_t st);
 double decode_tokens_time_us(const Geometry& g, int batch, int n_loaded);

@@ -27,8 +27,6 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
-#include <vector>
-
 #include <type_traits>
 
 #include "kernels.h"
@@ -67,7 +65,7 @@ extern "C" int bitstack_debug_trace(unsigned long long* host, int n) {
 #endif
 
 DecodeTuning& decode_tuning() {
-    static DecodeTuning t = {0, 0};
+    static DecodeTuning t;
     return t;
 }
 
@@ -206,7 +204,7 @@ struct RawT {
 };
 
 template <int KS>
-__global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode(KGroup grp) {
+__global__ __launch_bounds__((kConsumers + kProducers) * 64, 3) void k_decode_old(KGroup grp) {
     constexpr int NCH = KS / kChunkCols;   // sign chunks per slab
     constexpr int R = kTilesPerWave;       // 32-row tiles per consumer wavefront
     constexpr int RS = kDecodeRows;
@@ -817,19 +815,19 @@ static hipError_t launch_decode_t(KGroup& grp, int bg_req, hipStream_t st) {
                         96 * 4 + 16;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<KS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode_old<KS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(smem));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_decode<KS>), dim3(next), dim3((kConsumers + kProducers) * 64), smem, st, grp);
+    hipLaunchKernelGGL((k_decode_old<KS>), dim3(next), dim3((kConsumers + kProducers) * 64), smem, st, grp);
     return hipGetLastError();
 }
 
-hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st) {
+hipError_t launch_decode_group_old(const LaunchArgs* a, int count, hipStream_t st) {
     if (count < 1 || count > kMaxGroup) return hipErrorInvalidValue;
     const DecodeTuning& tn = decode_tuning();
-    int ks = tn.kslab;
+    int ks = tn.legacy_kslab;
     if (ks == 0) ks = a[0].geo.min_slab;
     KGroup grp;
     grp.count = count;
@@ -843,96 +841,11 @@ hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st) {
         grp.s[i].sign_bytes_total = unsigned(sign_span);
     }
     for (int i = count; i < kMaxGroup; ++i) grp.s[i] = grp.s[0];
-    if (ks == 1024) return launch_decode_t<1024>(grp, tn.bgroups, st);
-    if (ks == 512) return launch_decode_t<512>(grp, tn.bgroups, st);
-    if (ks == 256) return launch_decode_t<256>(grp, tn.bgroups, st);
+    if (ks == 1024) return launch_decode_t<1024>(grp, tn.bgroups.load(), st);
+    if (ks == 512) return launch_decode_t<512>(grp, tn.bgroups.load(), st);
+    if (ks == 256) return launch_decode_t<256>(grp, tn.bgroups.load(), st);
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_decode(const LaunchArgs& a, hipStream_t st) { return launch_decode_group(&a, 1, st); }
-
-// Estimated duration (microseconds) of one decode launch with m tokens of one stack: ~13 us +
-// the blocks a workgroup walks through at ~7.3 us per 1024 x 1024 signs, with the launcher's own
-// rule for the number of blocks per workgroup (one round of 256 workgroups, the shared
-// workspace).  0: the launcher would refuse (workspace too small for m tokens).
-static double decode_launch_time_us(const Geometry& g, int m, int n_loaded) {
-    const int ks = g.min_slab;
-    const int n_rs = (g.out + kDecodeRows - 1) / kDecodeRows, n_ks = g.in / ks, pairs = n_rs * n_ks;
-    double blocks = 0.0;   // per workgroup, times rounds
-    if (m == 1) {
-        int bg = 256 / pairs;
-        bg = bg < 1 ? 1 : bg > n_loaded ? n_loaded : bg;
-        blocks = double((n_loaded + bg - 1) / bg) * ((pairs * bg + 255) / 256);
-    } else {
-        for (int c = (m * pairs * n_loaded + 255) / 256; c <= n_loaded && blocks == 0.0; ++c) {
-            const int bg = (n_loaded + c - 1) / c;
-            if (m * pairs * bg <= 256 && m * n_ks * bg <= g.part_slots) blocks = c;
-        }
-        if (blocks == 0.0 && m * n_ks <= g.part_slots) blocks = double(n_loaded) * ((m * pairs + 255) / 256);
-        if (blocks == 0.0) return 0.0;
-    }
-    return 13.0 + blocks * 7.3 * ks / 1024.0;
-}
-
-// How a small batch is cut into launches of one to four tokens: the cut with the smallest
-// estimated total (three tokens of a tall stack are cheaper as 2 + 1 than as one launch whose
-// workgroups each walk the whole stack).  sizes[] receives the launch sizes in order; returns
-// the estimate.
-static double plan_decode_tokens(const Geometry& g, int batch, int n_loaded, int* sizes, int* n_launches) {
-    double t_of[kMaxGroup + 1] = {};
-    for (int m = 1; m <= kMaxGroup; ++m) t_of[m] = decode_launch_time_us(g, m, n_loaded);
-    // best[b]: cheapest way to run b tokens; take[b]: size of its last launch
-    std::vector<double> best(size_t(batch) + 1, 0.0);
-    std::vector<int> take(size_t(batch) + 1, 1);
-    for (int b = 1; b <= batch; ++b) {
-        best[b] = -1.0;
-        for (int m = 1; m <= kMaxGroup && m <= b; ++m) {
-            if (t_of[m] == 0.0) continue;
-            const double t = best[b - m] + t_of[m];
-            if (best[b] < 0.0 || t < best[b]) {
-                best[b] = t;
-                take[b] = m;
-            }
-        }
-    }
-    int n = 0;
-    for (int b = batch; b > 0; b -= take[b])
-        if (sizes) sizes[n++] = take[b];
-    if (n_launches) *n_launches = n;
-    return best[batch];
-}
-
-double decode_tokens_time_us(const Geometry& g, int batch, int n_loaded) {
-    return plan_decode_tokens(g, batch, n_loaded, nullptr, nullptr);
-}
-
-// A small batch through the decode kernel: one to four tokens per launch, each a member of the
-// group with its own x row, y row and share of the stack's workspace.
-hipError_t launch_decode_tokens(const LaunchArgs& a, hipStream_t st) {
-    const size_t xbytes = size_t(a.geo.in) * 2, ybytes = size_t(a.geo.out) * (a.y_f32 ? 4 : 2);
-    std::vector<int> sizes(size_t(a.batch));
-    int n_launches = 0;
-    plan_decode_tokens(a.geo, a.batch, a.n_loaded, sizes.data(), &n_launches);
-    int b = 0;
-    for (int l = 0; l < n_launches; ++l) {
-        const int count = sizes[l];
-        LaunchArgs t[kMaxGroup];
-        for (int i = 0; i < count; ++i) {
-            t[i] = a;
-            t[i].batch = 1;
-            t[i].x = static_cast<const unsigned char*>(a.x) + size_t(b + i) * xbytes;
-            t[i].y = static_cast<unsigned char*>(a.y) + size_t(b + i) * ybytes;
-        }
-        hipError_t e = launch_decode_group(t, count, st);
-        if (e == hipErrorInvalidValue && count > 1) {
-            // refused before anything was launched (e.g. a forced tuning the plan does not know): one by one
-            e = hipSuccess;
-            for (int i = 0; i < count && e == hipSuccess; ++i) e = launch_decode_group(t + i, 1, st);
-        }
-        if (e != hipSuccess) return e;
-        b += count;
-    }
-    return hipSuccess;
-}
 
 }  // namespace bitstack

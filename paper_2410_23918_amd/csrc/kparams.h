@@ -21,7 +21,8 @@ struct KParams {
     int n_bg;             // block groups: a workgroup walks blocks bg, bg + n_bg, ...
     unsigned* ctr;        // arrival counters (zero between calls)
     int out, in, batch, n_loaded;
-    int n_rs, n_ks;       // row slabs, column slabs per block
+    int n_rs, n_ks;       // row slabs, column ranges per block
+    int ks_chunks;        // 256-column chunks per column range (the last range may be shorter)
     int y_f32;
     __half* xpack;        // activation scratch in fragment order (null if the image has none)
     void* wdense;         // fp16 [out][in]: restored weight (materialising path only)
@@ -56,6 +57,7 @@ inline KParams make_params(const LaunchArgs& a) {
     p.batch = a.batch;
     p.n_loaded = a.n_loaded;
     p.n_rs = p.n_ks = 0;
+    p.ks_chunks = 0;
     p.y_f32 = a.y_f32 ? 1 : 0;
     p.xpack = a.geo.xpack_bytes ? reinterpret_cast<__half*>(a.image + a.geo.off_xpack) : nullptr;
     p.wdense = a.wdense;

@@ -35,7 +35,7 @@
 #include <stddef.h>
 #include <stdint.h>
 
-#if defined(__HIPCC__) || defined(__CUDACC__)
+#if defined(__HIPCC__)
 #define BS_HD __host__ __device__ inline
 #else
 #define BS_HD inline
@@ -47,7 +47,8 @@ constexpr int kRank = 16;
 constexpr int kTileRows = 32;      // rows per sign unit
 constexpr int kChunkCols = 256;    // columns per sign unit
 constexpr int kUnitBytes = 1024;
-constexpr int kCounterSlots = 4096; // split-accumulation arrival counters
+constexpr int kCounterSlots = 16384; // split-accumulation arrival counters (uint32 each)
+constexpr int kCounterStride = 32;   // the decode kernel keeps one counter per 128-byte line
 constexpr int kSmallBatch = 64;     // batches up to this size need no activation scratch
 
 struct Geometry {

@@ -112,21 +112,37 @@ def test_small_and_ragged_shapes(B, out, inn, n):
         err = O.relative_error(y, ref)
         print(f"{out}x{inn} panel kernel B=3 {dt}: {err:.2e}", flush=True)
         assert err <= TOL
-    min_slab = 1024 if inn % 1024 == 0 else 512 if inn % 512 == 0 else 256
-    for ks in (256, 512, 1024):
-        if inn % ks or ks < min_slab:
-            continue
-        for bg in (0, 1, n):
-            B.set_option(B.OPT_DECODE_KSLAB, ks)
-            B.set_option(B.OPT_DECODE_BGROUPS, bg)
-            try:
-                y1 = _run(B, ps, x[:1], n, B.KERNEL_DECODE)
-            finally:
-                B.set_option(B.OPT_DECODE_KSLAB, 0)
-                B.set_option(B.OPT_DECODE_BGROUPS, 0)
-            err = O.relative_error(y1, ref[:1])
-            print(f"{out}x{inn} ks={ks} bgroups={bg}: {err:.2e}", flush=True)
-            assert err <= TOL
+    # forced work splits of the decode kernel: rows per workgroup (tiles per wavefront), chunks per
+    # column range (ragged last ranges and last intervals included), block groups, early window
+    chunks = inn // 256
+    for tiles in (2, 4):
+        for ksc in sorted({1, 3, 4, 8, chunks} & set(range(1, min(chunks, 32) + 1))):
+            for bg in (0, 1, n):
+                for early in ((0, 1, 2, 4) if bg == 0 and ksc in (4, chunks) else (2,)):
+                    B.set_option(B.OPT_DECODE_TILES, tiles)
+                    B.set_option(B.OPT_DECODE_KS_CHUNKS, ksc)
+                    B.set_option(B.OPT_DECODE_BGROUPS, bg)
+                    B.set_option(B.OPT_DECODE_EARLY, early + 1)
+                    try:
+                        y1 = _run(B, ps, x[:1], n, B.KERNEL_DECODE)
+                    except B.BitStackError:
+                        y1 = None   # the stack's workspace has no room for this split: refused before any launch
+                    finally:
+                        for opt in (B.OPT_DECODE_TILES, B.OPT_DECODE_KS_CHUNKS, B.OPT_DECODE_BGROUPS, B.OPT_DECODE_EARLY):
+                            B.set_option(opt, 0)
+                    if y1 is None:
+                        assert ksc < 4   # only ranges narrower than the workspace was sized for
+                        continue
+                    err = O.relative_error(y1, ref[:1])
+                    print(f"{out}x{inn} tiles={tiles} ks_chunks={ksc} bgroups={bg} early={early}: {err:.2e}", flush=True)
+                    assert err <= TOL
+    # the producer/consumer kernel kept for comparison
+    B.set_option(B.OPT_DECODE_LEGACY, 1)
+    try:
+        y1 = _run(B, ps, x[:1], n, B.KERNEL_DECODE)
+    finally:
+        B.set_option(B.OPT_DECODE_LEGACY, 0)
+    assert O.relative_error(y1, ref[:1]) <= TOL
 
 
 @pytest.mark.parametrize("out,inn,n", [(1056, 768, 3), (96, 2048, 2)])
