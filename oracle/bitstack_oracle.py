@@ -23,6 +23,9 @@ Parity pins (tests/test_oracle_*.py, none of which re-types these formulas):
                          error, exact recovery at full rank, scale covariance
   forward_dense          brute-force triple loop, the factored form, linearity,
                          per-block additivity, closed-form rank-1 case
+  relative_error and its two companions (rms_relative_error,
+  damped_elementwise_error): hand-computed examples (different row maxima, a
+                         zero reference row, a negative peak), scale invariance
   Exact y values: parity unpinned by the paper (it prints no worked example);
   pinned only through the invariants above.
 """
@@ -278,3 +281,27 @@ def relative_error(y: np.ndarray, y_ref: np.ndarray) -> float:
     den = np.abs(y_ref).max(axis=-1)
     den = np.where(den == 0, 1.0, den)
     return float((num / den).max())
+
+
+def rms_relative_error(y: np.ndarray, y_ref: np.ndarray) -> float:
+    """Companion figure to relative_error: per token row
+    sqrt(mean_o (y - y_ref)^2) / sqrt(mean_o y_ref^2), worst row."""
+    y = np.asarray(y, dtype=np.float64)
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    num = np.sqrt(((y - y_ref) ** 2).mean(axis=-1))
+    den = np.sqrt((y_ref ** 2).mean(axis=-1))
+    den = np.where(den == 0, 1.0, den)
+    return float((num / den).max())
+
+
+def damped_elementwise_error(y: np.ndarray, y_ref: np.ndarray, damping: float = 1e-3) -> float:
+    """Companion figure to relative_error that also constrains small outputs:
+    max over elements of |y - y_ref| / (|y_ref| + damping * max_o |y_ref|), per token
+    row, worst row.  (A pure element-wise relative error is meaningless next to the
+    zeros of y_ref.)"""
+    y = np.asarray(y, dtype=np.float64)
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    peak = np.abs(y_ref).max(axis=-1, keepdims=True)
+    peak = np.where(peak == 0, 1.0, peak)
+    return float((np.abs(y - y_ref) / (np.abs(y_ref) + damping * peak)).max())
+

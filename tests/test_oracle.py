@@ -276,3 +276,45 @@ def test_synthetic_blocks_have_the_documented_structure():
     m0 = np.abs(U[0].astype(float) @ V[0].astype(float).T).mean()
     m2 = np.abs(U[2].astype(float) @ V[2].astype(float).T).mean()
     assert m2 < m0
+
+
+# ---------------------------------------------------------------------------
+# The parity metric itself (the reading of "maximum relative error 2e-3": per
+# token row max |y - y_ref| / max |y_ref|), pinned on values worked out by hand.
+# ---------------------------------------------------------------------------
+def test_relative_error_hand_examples():
+    ref = np.array([[1.0, -4.0, 2.0],        # peak 4 (negative entry)
+                    [0.5, 0.25, -0.125]])    # peak 0.5
+    y = np.array([[1.0, -4.0, 2.2],          # largest deviation 0.2  -> 0.2 / 4   = 0.05
+                  [0.5, 0.30, -0.125]])      # largest deviation 0.05 -> 0.05 / 0.5 = 0.1
+    assert O.relative_error(y, ref) == pytest.approx(0.1, rel=1e-12)
+    # every row is judged against its own peak: swapping the deviations changes the figure
+    y2 = np.array([[1.0, -4.0, 2.05], [0.5, 0.45, -0.125]])   # 0.0125 and 0.4
+    assert O.relative_error(y2, ref) == pytest.approx(0.4, rel=1e-12)
+    # one row only, deviation at the (negative) peak itself
+    assert O.relative_error(np.array([[1.0, -3.0, 2.0]]), ref[:1]) == pytest.approx(0.25, rel=1e-12)
+    # a zero reference row: the deviation itself (denominator 1), not a division by zero
+    z = np.zeros((1, 3))
+    assert O.relative_error(np.array([[0.0, 0.0, 0.0]]), z) == 0.0
+    assert O.relative_error(np.array([[0.0, -0.25, 0.0]]), z) == pytest.approx(0.25, rel=1e-12)
+    # 1-D inputs are one row; exact match is zero; a common factor on both cancels
+    assert O.relative_error(ref[0], ref[0]) == 0.0
+    assert O.relative_error(7.0 * y, 7.0 * ref) == pytest.approx(0.1, rel=1e-12)
+    # not symmetric in its arguments: the reference supplies the denominator
+    assert O.relative_error(ref, y) == pytest.approx(0.05 / 0.5, rel=1e-12)
+    assert O.relative_error(np.array([[8.0, 0.0]]), np.array([[4.0, 0.0]])) == pytest.approx(1.0)
+    assert O.relative_error(np.array([[4.0, 0.0]]), np.array([[8.0, 0.0]])) == pytest.approx(0.5)
+
+
+def test_companion_error_figures_hand_examples():
+    ref = np.array([[3.0, -4.0], [0.0, 2.0]])
+    y = np.array([[3.0, -3.0], [0.1, 2.0]])
+    # rms: row 0 sqrt(0.5) / sqrt(12.5) = 0.2; row 1 sqrt(0.005) / sqrt(2) = 0.05
+    assert O.rms_relative_error(y, ref) == pytest.approx(0.2, rel=1e-12)
+    # damped element-wise, damping 0.5: row 0 -> 1 / (4 + 2) = 1/6; row 1 -> 0.1 / (0 + 1) = 0.1
+    assert O.damped_elementwise_error(y, ref, damping=0.5) == pytest.approx(1.0 / 6.0, rel=1e-12)
+    # default damping 1e-3: the small reference entry dominates: 0.1 / (0 + 0.002) = 50
+    assert O.damped_elementwise_error(y, ref) == pytest.approx(50.0, rel=1e-12)
+    assert O.rms_relative_error(ref, ref) == 0.0 and O.damped_elementwise_error(ref, ref) == 0.0
+    assert O.rms_relative_error(np.array([[0.0, 0.5]]), np.zeros((1, 2))) == pytest.approx(np.sqrt(0.125))
+
