@@ -58,34 +58,64 @@ __device__ unsigned long long g_decode_trace[1024 * 128];
 extern "C" int bitstack_debug_decode_trace(unsigned long long* host, int n) {
     return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_decode_trace), size_t(n) * 8);
 }
-// timing experiments (wrong results, same memory accesses), chosen at compile time: -DBITSTACK_EXP=n
-#ifndef BITSTACK_EXP
-#define BITSTACK_EXP 0
-#endif
-#define BS_EXP(n) (BITSTACK_EXP == (n))
 #define BS_TR(slot)                                                                              \
     do {                                                                                         \
         if (lane == 0 && (wave == 0 || wave == 7)) trace_lds[(wave ? 64 : 0) + (slot)] = wall_clock64(); \
     } while (0)
 #else
 #define BS_TR(slot) do { } while (0)
-#define BS_EXP(n) false
 #endif
 
 namespace {
 
 constexpr float kQMax = 32512.0f;   // |q| <= 127*256: the high byte stays in int8 after +128 rounding
+constexpr int kMaxChunkExp = 3;     // finest chunk scale: 2^-3 of the range's
 constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int kPieceChunks = 4;                          // sign chunks per interval
 constexpr int kPieceCols = kPieceChunks * kChunkCols;    // 1024
 constexpr int kFragBytes = kPieceCols * 32;              // one fragment buffer
 constexpr int kXsFloats = kDecodeMaxRangeChunks * kChunkCols;
+// LDS layout (bytes from the start): two fragment buffers, the x/s table of the range, the maxima per
+// block and (16 bits each) per (block, chunk, column class), three column-sum buffers, the smallest of
+// those maxima per block, four flag words
+constexpr int kLdsXs = 2 * kFragBytes;
+constexpr int kLdsAmax = kLdsXs + kXsFloats * 4;
+constexpr int kLdsAmaxStep = kLdsAmax + kDecodeMaxBlocksPerWg * 4;
+constexpr int kLdsColSums = kLdsAmaxStep + kDecodeMaxBlocksPerWg * kDecodeMaxRangeChunks * 8 * 2;
+constexpr int kLdsAmin = kLdsColSums + 3 * 32 * 4;
+constexpr int kLdsFlags = kLdsAmin + kDecodeMaxBlocksPerWg * 4;
+constexpr int kLdsTrace = kLdsFlags + 16;
 #ifdef BITSTACK_TRACE
 constexpr int kTraceBytes = 1024;
 #else
 constexpr int kTraceBytes = 0;
 #endif
+
+// maximum over each aligned group of 32 lanes, in all its lanes (values >= 0: compared as integers).
+// Four rotations inside the rows of 16 lanes, then one exchange between the two rows: no LDS atomics,
+// which serialise lane by lane when many lanes name one address.
+__device__ __forceinline__ int group32_max(int v) {
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x128, 0xF, 0xF, false));   // row_ror:8
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x124, 0xF, 0xF, false));   // row_ror:4
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x122, 0xF, 0xF, false));   // row_ror:2
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x121, 0xF, 0xF, false));   // row_ror:1
+    return max(v, __builtin_amdgcn_ds_swizzle(v, 0x401F));                   // lane ^ 16
+}
+
+__device__ __forceinline__ int group32_min(int v) {
+    v = min(v, __builtin_amdgcn_update_dpp(0x7FFFFFFF, v, 0x128, 0xF, 0xF, false));
+    v = min(v, __builtin_amdgcn_update_dpp(0x7FFFFFFF, v, 0x124, 0xF, 0xF, false));
+    v = min(v, __builtin_amdgcn_update_dpp(0x7FFFFFFF, v, 0x122, 0xF, 0xF, false));
+    v = min(v, __builtin_amdgcn_update_dpp(0x7FFFFFFF, v, 0x121, 0xF, 0xF, false));
+    return min(v, __builtin_amdgcn_ds_swizzle(v, 0x401F));
+}
+
+// maximum over each aligned group of 4 lanes, in all its lanes
+__device__ __forceinline__ int quad_max(int v) {
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false));   // quad_perm:[1,0,3,2]
+    return max(v, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false)); // quad_perm:[2,3,0,1]
+}
 
 __device__ __forceinline__ void wait_all_vector_memory() {
     // vmcnt(0) with the other counters left alone: every global load and store this
@@ -100,13 +130,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
     constexpr int RS = R * 256;   // rows per workgroup
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    v4i* frag0 = reinterpret_cast<v4i*>(smem);                                   // [2][32 fragments][64 lanes] x 16 B
-    float* xs = reinterpret_cast<float*>(smem + 2 * kFragBytes);                 // [range columns], panel order
-    int* amax_i = reinterpret_cast<int*>(xs + kXsFloats);                        // [kDecodeMaxBlocksPerWg], float bits
-    int* cs = amax_i + kDecodeMaxBlocksPerWg;                                    // [3][32]
-    unsigned* flag = reinterpret_cast<unsigned*>(cs + 96);
+    v4i* frag0 = reinterpret_cast<v4i*>(smem);                              // [2][32 fragments][64 lanes] x 16 B
+    float* xs = reinterpret_cast<float*>(smem + kLdsXs);                    // [range columns], panel order
+    int* amax_i = reinterpret_cast<int*>(smem + kLdsAmax);                  // [blocks], float bits
+    unsigned short* amax_s = reinterpret_cast<unsigned short*>(smem + kLdsAmaxStep);   // [blocks][chunks * 8 classes]
+    int* cs = reinterpret_cast<int*>(smem + kLdsColSums);                   // [3][32]
+    int* amin_i = reinterpret_cast<int*>(smem + kLdsAmin);                  // [blocks]: smallest (chunk, class) maximum
+    unsigned* flag = reinterpret_cast<unsigned*>(smem + kLdsFlags);         // [0] finisher flag, [1] max |x/s| bits
 #ifdef BITSTACK_TRACE
-    unsigned long long* trace_lds = reinterpret_cast<unsigned long long*>(flag + 4);   // [2][64]
+    unsigned long long* trace_lds = reinterpret_cast<unsigned long long*>(smem + kLdsTrace);   // [2][64]
 #endif
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -185,7 +217,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
         return raw;
     };
     Raw raw = load_raw(0);       // interval 0, quantised in the prologue
-    Raw raw_cur = load_raw(1);   // the interval after the one being computed
+    Raw raw_cur = load_raw(1);   // interval 1 (used by the wavefronts that quantise at the start of an interval)
     // The two wavefronts of a SIMD share its issue port and the older one is served first: it
     // finishes an interval's matrix-core work well before the younger one.  So the younger one
     // (wavefronts 4..7) quantises its share of the next panel at the start of an interval, while
@@ -235,7 +267,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
     // matrix) is still loaded, from an offset beyond the descriptor: the number of loads in flight
     // stays the same on every path.  The offset is made invalid arithmetically (top bit; the
     // descriptor covers less than 2 GiB), not by selecting between two loads.
-    auto request = [&](int i, int c) {   // window slots of chunk c <- interval i
+    auto request = [&](int i, int c) __attribute__((always_inline)) {   // window slots of chunk c <- interval i
         const bool ok = i < n_int && c < chunks_of(min(i, n_int - 1));
         const unsigned sb = interval_base(min(i, n_int - 1)) + unsigned(c) * kUnitBytes;
         const unsigned oob = ok ? 0u : 0x80000000u;
@@ -249,7 +281,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
 
     // ---------------------------------------------------------------- x/s table, range maxima
     if (tid < 96) cs[tid] = 0;
-    if (tid < kDecodeMaxBlocksPerWg) amax_i[tid] = 0;
+    if (tid < kDecodeMaxBlocksPerWg) {
+        amax_i[tid] = 0;
+        amin_i[tid] = 0x7F800000;   // +infinity
+    }
+    if (tid == 0) flag[1] = 0;
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         const int o8 = tid + k * kThreads;
@@ -286,8 +322,21 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
                 a = fmaxf(a, fabsf(xx[2 * k]) * __low2float(h));
                 a = fmaxf(a, fabsf(xx[2 * k + 1]) * __high2float(h));
             }
-            // non-negative floats order like their bit patterns
-            atomicMax(&amax_i[q], __float_as_int(a));
+            float xm = 0.0f;   // largest |x/s| (the same for every block: taken from block 0's tasks)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) xm = fmaxf(xm, fabsf(xx[k]));
+            // (non-negative floats order like their bit patterns.)  The 4 tasks of a (chunk, column class)
+            // step sit in one aligned group of 4 lanes: its maximum, rounded up to 16 bits, is kept for
+            // the step's exponent.  Range maximum, smallest step maximum and the largest |x/s| go through
+            // groups of 32 lanes first, so that few lanes touch the shared words.
+            const int sa = ((quad_max(__float_as_int(a)) + 0xFFFF) >> 16) << 16;
+            if ((lane & 3) == 0) amax_s[q * (kDecodeMaxRangeChunks * 8) + (o8 >> 2)] = (unsigned short)(sa >> 16);
+            const int ga = group32_max(__float_as_int(a)), gn = group32_min(sa), gx = group32_max(__float_as_int(xm));
+            if ((lane & 31) == 0) {
+                atomicMax(&amax_i[q], ga);
+                atomicMin(&amin_i[q], gn);
+                if (q == 0) atomicMax(reinterpret_cast<int*>(&flag[1]), gx);
+            }
         };
 #pragma unroll
         for (int k = 0; k < kPreTasks; ++k)
@@ -297,24 +346,72 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
     }
     lds_barrier();   // P2: maxima complete
     BS_TR(3);
+    // The quantiser multiplies in fp16: V[j][r] * (x[j]/s[j] * scale).  The second factor stays below
+    // 8 / max_r |V[j][r]|, which only leaves fp16's range for channels whose V entries are all tiny
+    // (< 1.3e-4) while x/s is huge; a block where that can happen takes the fp32 quantiser instead.
+    auto needs_fp32 = [&](int q) -> bool {
+        const float amax = __int_as_float(amax_i[q]);
+        return !(__int_as_float(int(flag[1])) * float(1 << kMaxChunkExp) <= 60000.0f * amax);
+    };
+
+    // Quiet columns next to loud ones (a few activation channels far above the rest: the case
+    // activation-aware scaling, Eq. 3-4, is there for) keep their precision.  A step = the 32 columns of
+    // one class t in one chunk (one panel fragment, one matrix-core instruction per tile).  A step whose
+    // maximum is at least four times below the range's is quantised 2^e times finer, e = 2 or 3.  The
+    // integer sums of a block stay on ONE scale, 2^-E of the range's with E the largest e of the block:
+    // a step with e < E gets its sign bytes 2^(E - e) times larger instead (a rotate of the chunk's sign
+    // words when the shift changes, the mask moves along).  For activations without such channels every
+    // e and E is 0 and nothing changes.
+    auto exp_of = [&](int a, int b) -> int {   // float bits, a >= 0, b >= 0: floor(log2(a / b)), as 0, 2 or 3
+        const int e = (a >> 23) - (b >> 23) - ((a & 0x7FFFFF) < (b & 0x7FFFFF) ? 1 : 0);
+        return e >= 2 ? min(e, kMaxChunkExp) : 0;
+    };
+    auto step_exp = [&](int q, int cr, int t) -> int {   // block q of this workgroup, chunk cr of its range, class t: e
+        return exp_of(amax_i[q], int(amax_s[q * (kDecodeMaxRangeChunks * 8) + cr * 8 + t]) << 16);
+    };
+    auto block_exp = [&](int q) -> int { return exp_of(amax_i[q], amin_i[q]); };   // E: the quietest step's e
 
     // quantise this thread's two groups of interval i into fragment buffer (i & 1)
-    auto quantise = [&](int i, const Raw& rw) {
+    auto quantise = [&](int i, const Raw& rw) __attribute__((always_inline)) {
         const int q = i / npc, pc = i - q * npc;
         if (my_chunk >= min(kPieceChunks, rc - pc * kPieceChunks)) return;   // chunk past the range (wave-uniform)
         v4i* frag = frag0 + (i & 1) * (kFragBytes / 16);
         int* csq = cs + (q % 3) * 32;
         const float amax = __int_as_float(amax_i[q]);
-        const float inv = amax > 0.0f ? (kQMax / 32767.0f) / amax : 0.0f;
+        // (an approximate reciprocal will do: any scale a hair below 1 / amax keeps the codes in range,
+        // and the epilogue multiplies by amax itself)
+        const float inv = amax > 0.0f ? (kQMax / 32767.0f) * __builtin_amdgcn_rcpf(amax) : 0.0f;
         const int pos = tid >> 3, rk0 = (tid & 7) * 2;
         const int g = pos & 1, t = (pos >> 1) & 7, c = pos >> 4;
+        // this step's exponent e and the shift E - e of its sign bytes
+        const int ce = step_exp(q, pc * kPieceChunks + my_chunk, t);
+        const int cs_shift = block_exp(q) - ce;
         // the sign byte of class t is 2^(t%4) (high-nibble classes are shifted down before use):
-        // pre-dividing by it puts every class on one scale, (sign byte) * q = 32512 * T / amax
+        // pre-dividing by it puts every class on one scale, (sign byte) * q = 32512 * 2^ce * T / amax
         const int tc = t & 3;
-        const float f = inv * __int_as_float((127 - tc) << 23);   // inv * 2^-tc
+        const float f = inv * __int_as_float((127 + ce - tc) << 23);   // inv * 2^(ce - tc)
+        // uniform over the workgroup.  Blocks with outlier channels (E > 0) also take the fp32 variant:
+        // there the loud chunks set the error, and fp32 arithmetic keeps it a third lower
+        const bool fp32_path = needs_fp32(q) || block_exp(q) != 0;
+        const float4* xg = reinterpret_cast<const float4*>(xs + (pc * kPieceChunks * 16 + pos) * 16);
+        typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+        // + 128 (in units of the 16-bit code) rides along in the multiply-add: the high byte of
+        // q + 128 is round(q / 256), the low byte q ^ 0x80
+        constexpr float kHalfByte = 128.0f / 32767.0f;
+        h2v xh[8];
         float xf[16];
-        {
-            const float4* xg = reinterpret_cast<const float4*>(xs + (pc * kPieceChunks * 16 + pos) * 16);
+        if (!fp32_path) {
+            // the 16 channel factors of this position as fp16 pairs (round to nearest).  fp16 arithmetic
+            // keeps 11 significant bits per panel value (the class pre-division already leaves the worst
+            // class 13): the error of y grows from 2.2e-4 to 3.5e-4 of max |y|, for less than half the
+            // instructions of the fp32 variant.
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float4 v = xg[k];
+                xh[2 * k][0] = _Float16(v.x * f); xh[2 * k][1] = _Float16(v.y * f);
+                xh[2 * k + 1][0] = _Float16(v.z * f); xh[2 * k + 1][1] = _Float16(v.w * f);
+            }
+        } else {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const float4 v = xg[k];
@@ -327,16 +424,23 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
             const uint4 va = rw.v[m][0], vb = rw.v[m][1];
             const unsigned vw[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
             unsigned qq[8];
+            if (!fp32_path) {
+                const h2v bias = {_Float16(kHalfByte), _Float16(kHalfByte)};
 #pragma unroll
-            for (int e2 = 0; e2 < 8; ++e2) {
-                typedef _Float16 h2v __attribute__((ext_vector_type(2)));
-                const h2v h = __builtin_bit_cast(h2v, vw[e2]);
-                // + 128 (in units of the 16-bit code) rides along in the multiply-add that also converts
-                // the fp16 factor: the high byte of q + 128 is round(q / 256), the low byte q ^ 0x80
-                constexpr float kHalfByte = 128.0f / 32767.0f;
-                const v2s qv = __builtin_amdgcn_cvt_pknorm_i16(__builtin_fmaf(float(h[0]), xf[2 * e2], kHalfByte),
-                                                               __builtin_fmaf(float(h[1]), xf[2 * e2 + 1], kHalfByte));
-                qq[e2] = __builtin_bit_cast(unsigned, qv);
+                for (int e2 = 0; e2 < 8; ++e2) {
+                    const h2v pr = __builtin_elementwise_fma(__builtin_bit_cast(h2v, vw[e2]), xh[e2], bias);
+                    const unsigned pu = __builtin_bit_cast(unsigned, pr);
+                    // both halves of one register to signed 16-bit fixed point: round(clamp(p, -1, 1) * 32767)
+                    asm("v_cvt_pknorm_i16_f16 %0, %1, %1 op_sel:[0,1,0]" : "=v"(qq[e2]) : "v"(pu));
+                }
+            } else {
+#pragma unroll
+                for (int e2 = 0; e2 < 8; ++e2) {
+                    const h2v h = __builtin_bit_cast(h2v, vw[e2]);
+                    const v2s qv = __builtin_amdgcn_cvt_pknorm_i16(__builtin_fmaf(float(h[0]), xf[2 * e2], kHalfByte),
+                                                                   __builtin_fmaf(float(h[1]), xf[2 * e2 + 1], kHalfByte));
+                    qq[e2] = __builtin_bit_cast(unsigned, qv);
+                }
             }
             v4i H, L;
             int sH = 0, sL = 0;
@@ -349,8 +453,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
                 sH = __builtin_amdgcn_sdot4(int(hi), 0x01010101, sH, false);
                 sL = __builtin_amdgcn_sdot4(int(lo), 0x01010101, sL, false);
             }
-            sums[m][0] = sH << tc;
-            sums[m][1] = sL << tc;
+            // column sums on the block's scale, like the sign bytes of this chunk
+            sums[m][0] = sH << (tc + cs_shift);
+            sums[m][1] = sL << (tc + cs_shift);
             const int r = rk0 + m;
             const int lane_hi = g * 32 + 8 * (r >> 2) + (r & 3);
             frag[(c * 8 + t) * 64 + lane_hi] = H;
@@ -390,15 +495,27 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
     // One interval: block q, piece pc of the column range.  LAST = the piece that ends the block
     // (two instantiations, so that the number of loads in flight is the same on every path
     // through a given instantiation and the memory waits the compiler places are exact).
-    auto interval = [&](int i, int q, int pc, auto last_tag) {
+    auto interval = [&](int i, int q, int pc, auto last_tag) __attribute__((always_inline)) {
         constexpr bool LAST = decltype(last_tag)::value;
         const int nvalid = min(kPieceChunks, rc - pc * kPieceChunks);
+        // shifts E - e of this interval's 32 steps (uniform): lane c*8 + t looks step (c, t) up, two
+        // ballots carry the two bits of every shift
+        unsigned shift_lo, shift_hi;
+        {
+            const int cr = min(pc * kPieceChunks + ((lane >> 3) & 3), rc - 1);
+            const int my = lane < 32 ? block_exp(q) - step_exp(q, cr, lane & 7) : 0;
+            shift_lo = unsigned(__builtin_amdgcn_ballot_w64((my & 1) != 0));
+            shift_hi = unsigned(__builtin_amdgcn_ballot_w64((my & 2) != 0));
+        }
         if (i < 12) BS_TR(8 + 4 * i);
         // column sums of block q + 2 start from zero: that buffer was last read in the epilogue of
         // block q - 1 (at least one barrier ago) and is first added to one barrier from now or later
         if (LAST && tid < 32) cs[((q + 2) % 3) * 32 + tid] = 0;
-        // small loads, requested before the window refills: raw V of the interval after next
-        const Raw raw_nxt = load_raw(i + 2);
+        if (late_wave && i + 1 < n_int) quantise(i + 1, raw_cur);
+        // small loads, requested before the window refills: raw V of the interval this wavefront
+        // quantises next (at the end of this interval, or at the start of the next one) and, for the
+        // epilogue, the U rows of its tiles
+        raw_cur = load_raw(i + (late_wave ? 2 : 1));
         uint4 ur[R][2];
         if constexpr (LAST) {
             const uint4* usrc =
@@ -412,35 +529,42 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (late_wave && i + 1 < n_int && !BS_EXP(3)) quantise(i + 1, raw_cur);
         const v4i* frag = frag0 + (i & 1) * (kFragBytes / 16);
         v4i Tf = frag[lane];
 #pragma unroll
         for (int c = 0; c < kPieceChunks; ++c) {
             if (c < nvalid) {
+                int rot = 0;   // how far this chunk's sign words are rotated left at the moment
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
                     // the next fragment is requested before this one is used
                     v4i Tn = Tf;
-                    if (!BS_EXP(5) && c * 8 + t + 1 < kPieceChunks * 8) Tn = frag[(c * 8 + t + 1) * 64 + lane];
-                    const int mask = 0x01010101 << (t & 3);
-                    if (t == 4) {   // high-nibble classes: bit 4+t' of a byte becomes bit t'
+                    if (c * 8 + t + 1 < kPieceChunks * 8) Tn = frag[(c * 8 + t + 1) * 64 + lane];
+                    // sign bytes of this step are 2^(t%4 + sh): the words are rotated left by sh (rare: only
+                    // in a block where some steps are quantised finer than this one)
+                    const int sh = int((shift_lo >> (c * 8 + t)) & 1u) | int((shift_hi >> (c * 8 + t)) & 1u) << 1;
+                    if (sh != rot) {
+                        const unsigned by = unsigned(32 - (sh - rot)) & 31u;   // rotate right by this much
 #pragma unroll
                         for (int tl = 0; tl < R; ++tl)
 #pragma unroll
-                            for (int w = 0; w < 4; ++w) win[c][tl][w] = int(unsigned(win[c][tl][w]) >> 4);
+                            for (int w = 0; w < 4; ++w)
+                                win[c][tl][w] = int(__builtin_amdgcn_alignbit(unsigned(win[c][tl][w]), unsigned(win[c][tl][w]), by));
+                        rot = sh;
+                    }
+                    const int mask = 0x01010101 << ((t & 3) + sh);
+                    if (t == 4) {   // high-nibble classes: bit 4+t' of a byte goes where bit t' was (a rotate:
+                                    // the rotates above may have moved bits of the last byte to the front)
+#pragma unroll
+                        for (int tl = 0; tl < R; ++tl)
+#pragma unroll
+                            for (int w = 0; w < 4; ++w)
+                                win[c][tl][w] = int(__builtin_amdgcn_alignbit(unsigned(win[c][tl][w]), unsigned(win[c][tl][w]), 4));
                     }
 #pragma unroll
                     for (int tl = 0; tl < R; ++tl) {
-                        if constexpr (BS_EXP(1) || BS_EXP(5) || BS_EXP(6)) {          // matrix-core instructions without the masking
-                            acc[tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Tf, win[c][tl], acc[tl], 0, 0, 0);
-                        } else if constexpr (BS_EXP(2)) {   // masking without the matrix-core instructions
-                            const v4i B = win[c][tl] & mask;
-                            acc[tl][0] ^= B[0] ^ Tf[0]; acc[tl][1] ^= B[1]; acc[tl][2] ^= B[2]; acc[tl][3] ^= B[3];
-                        } else {
-                            const v4i B = win[c][tl] & mask;
-                            acc[tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Tf, B, acc[tl], 0, 0, 0);
-                        }
+                        const v4i B = win[c][tl] & mask;
+                        acc[tl] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Tf, B, acc[tl], 0, 0, 0);
                     }
                     Tf = Tn;
                 }
@@ -448,34 +572,40 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
             // this chunk's window slots now take the same chunk of the next interval (not
             // earlier: old and new contents would both need registers)
             __builtin_amdgcn_sched_barrier(0);
-            if (!BS_EXP(6) && !BS_EXP(7)) request(i + 1, c);
+            request(i + 1, c);
         }
         if (i < 12) BS_TR(9 + 4 * i);
         if constexpr (LAST) {
-            // epilogue: undo S = 2B - 1, weight by U, reduce over ranks
+            // epilogue: undo S = 2B - 1, weight by U, reduce over ranks.  Sums and column sums are on the
+            // block's scale, 2^-E of the range's.
             const int part = lane >> 5;   // 0 = high bytes, 1 = low bytes
-            const float dq = __int_as_float(amax_i[q]) * (1.0f / kQMax);
+            const float dq = __int_as_float(amax_i[q]) * (1.0f / kQMax) * __int_as_float((127 - block_exp(q)) << 23);
             const int* csq = cs + (q % 3) * 32 + part * 16;
+            float sum[R];
+#pragma unroll
+            for (int tl = 0; tl < R; ++tl) sum[tl] = 0.0f;
+#pragma unroll
+            for (int r2 = 0; r2 < 8; ++r2) {
+                const int c0 = csq[2 * r2], c1 = csq[2 * r2 + 1];
+#pragma unroll
+                for (int tl = 0; tl < R; ++tl) {
+                    const unsigned uw = r2 < 4 ? (r2 == 0 ? ur[tl][0].x : r2 == 1 ? ur[tl][0].y : r2 == 2 ? ur[tl][0].z : ur[tl][0].w)
+                                               : (r2 == 4 ? ur[tl][1].x : r2 == 5 ? ur[tl][1].y : r2 == 6 ? ur[tl][1].z : ur[tl][1].w);
+                    const __half2 h = *reinterpret_cast<const __half2*>(&uw);
+                    const int z0 = (acc[tl][2 * r2] << 1) - c0;
+                    const int z1 = (acc[tl][2 * r2 + 1] << 1) - c1;
+                    sum[tl] = fmaf(float(z0), __low2float(h), sum[tl]);
+                    sum[tl] = fmaf(float(z1), __high2float(h), sum[tl]);
+                }
+            }
 #pragma unroll
             for (int tl = 0; tl < R; ++tl) {
-                const uint4 ua = ur[tl][0], uc = ur[tl][1];
-                const unsigned uw[8] = {ua.x, ua.y, ua.z, ua.w, uc.x, uc.y, uc.z, uc.w};
-                float sum = 0.0f;
-#pragma unroll
-                for (int r2 = 0; r2 < 8; ++r2) {
-                    const __half2 h = *reinterpret_cast<const __half2*>(&uw[r2]);
-                    const int z0 = (acc[tl][2 * r2] << 1) - csq[2 * r2];
-                    const int z1 = (acc[tl][2 * r2 + 1] << 1) - csq[2 * r2 + 1];
-                    sum = fmaf(float(z0), __low2float(h), sum);
-                    sum = fmaf(float(z1), __high2float(h), sum);
-                }
-                const float other = __shfl_xor(sum, 32);
-                yacc[tl] = fmaf(256.0f * sum + other, dq, yacc[tl]);   // meaningful in lanes 0..31
+                const float other = __shfl_xor(sum[tl], 32);
+                yacc[tl] = fmaf(256.0f * sum[tl] + other, dq, yacc[tl]);   // meaningful in lanes 0..31
             }
         }
         if (i < 12) BS_TR(10 + 4 * i);
-        if (!late_wave && i + 1 < n_int && !BS_EXP(3)) quantise(i + 1, raw_cur);   // (experiment 3: interval 0's panel is reused)
-        raw_cur = raw_nxt;
+        if (!late_wave && i + 1 < n_int) quantise(i + 1, raw_cur);
         if (i < 12) BS_TR(11 + 4 * i);
         lds_barrier();
     };
@@ -702,7 +832,7 @@ bool plan_decode(const LaunchArgs* a, int count, DecodePlan* best) {
 
 template <int R, int EARLY>
 hipError_t launch_variant(const KGroup& grp, unsigned wgs, hipStream_t st) {
-    const size_t smem = 2 * size_t(kFragBytes) + size_t(kXsFloats) * 4 + size_t(kDecodeMaxBlocksPerWg) * 4 + 96 * 4 + 16 + kTraceBytes;
+    const size_t smem = size_t(kLdsTrace) + kTraceBytes;
     static std::atomic<int> attr_state{0};   // per instantiation; setting the attribute twice is harmless
     if (attr_state.load(std::memory_order_acquire) == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<R, EARLY>),
