@@ -275,6 +275,24 @@ int bitstack_decompose(const float* W, const float* s, int out, int in, int k, i
                        uint32_t* sign_words, uint16_t* U, uint16_t* V, void* workspace,
                        size_t workspace_bytes, bitstack_stream_t stream);
 
+/* For callers that cannot allocate or lend device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): bitstack_linear
+ * for one token with the split-accumulation workspace (partial rows, arrival
+ * counters) in a static device array of the library instead of the stack's own
+ * buffer.  Calls no allocating routine.  bitstack_static_workspace_bytes() is the
+ * size of that array (4 MiB of partial rows + 64 KiB of counters); every GPU the
+ * library runs on holds its own copy until the process ends.
+ *   x, y, blocks, n_loaded, stream: as bitstack_linear (fp16 in, fp16 out).
+ * BITSTACK_E_BUFSIZE when the stack's partial rows cannot fit the array in any
+ * work split (out * 4 bytes * ceil(in / 8192) > 4 MiB): nothing is enqueued.
+ * All calls on one GPU share the array: two calls that overlap in time on one
+ * GPU (different streams, different threads) race, whatever their stacks; calls
+ * on one stream are ordered and safe.  Same results as bitstack_linear up to the
+ * order of the fp32 partial sums (the work split may differ). */
+size_t bitstack_static_workspace_bytes(void);
+int bitstack_linear_static(const void* x, const bitstack_weight_t* blocks, int n_loaded, void* y,
+                           bitstack_stream_t stream);
+
 /* Shape queries on a handle. */
 int bitstack_weight_shape(const bitstack_weight_t* w, int* out, int* in, int* k, int* n,
                           int* max_batch);

@@ -54,6 +54,10 @@ def lib():
     L.bitstack_weight_shape.argtypes = [vp] + [C.POINTER(i32)] * 5
     L.bitstack_linear_many.argtypes = [vp, i32, i32, vp]
     L.bitstack_linear_many.restype = i32
+    L.bitstack_linear_static.argtypes = [vp, vp, i32, vp, vp]
+    L.bitstack_linear_static.restype = i32
+    L.bitstack_static_workspace_bytes.restype = sz
+    L.bitstack_static_workspace_bytes.argtypes = []
     L.bitstack_set_option.argtypes = [i32, i32]
     L.bitstack_probe_read.argtypes = [vp, sz, vp, i32, vp]
     L.bitstack_probe_read.restype = i32
@@ -363,6 +367,15 @@ class PackedStack:
             y = torch.empty(self.out, dtype=torch.float16, device=self.device)
         _check(lib().bitstack_linear(x.data_ptr(), self._h, n_loaded, y.data_ptr(), self._stream(stream)),
                "bitstack_linear")
+        return y
+
+    def linear_static(self, x, n_loaded: int, y=None, stream=None):
+        """bitstack_linear_static: one token, workspace in the library's static device array."""
+        import torch
+        if y is None:
+            y = torch.empty(self.out, dtype=torch.float16, device=self.device)
+        _check(lib().bitstack_linear_static(x.data_ptr(), self._h, n_loaded, y.data_ptr(), self._stream(stream)),
+               "bitstack_linear_static")
         return y
 
     def linear_batched(self, x, n_loaded: int, y=None, out_dtype=None, kernel: int = KERNEL_AUTO, stream=None):

@@ -779,11 +779,12 @@ bool plan_decode(const LaunchArgs* a, int count, DecodePlan* best) {
                 for (int i = 0; i < count; ++i) {
                     int slots = 0, ctrs = 0;
                     for (int j = 0; j < count; ++j)
-                        if (a[j].image == a[i].image) {
+                        if (a[j].image == a[i].image && a[j].ws_part == a[i].ws_part) {
                             slots += pl.m[j].n_ks * ((a[j].n_loaded + T - 1) / T);
                             ctrs += pl.m[j].n_rs;
                         }
-                    if (slots > a[i].geo.part_slots || ctrs * kCounterStride > kCounterSlots) return false;
+                    const int have = a[i].ws_part ? a[i].ws_part_slots : a[i].geo.part_slots;
+                    if (slots > have || ctrs * kCounterStride > kCounterSlots) return false;
                 }
                 return true;
             };
@@ -873,7 +874,7 @@ hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st) {
         // behind those of the members before it.
         int slots_before = 0, ctrs_before = 0;
         for (int j = 0; j < i; ++j)
-            if (a[j].image == a[i].image) {
+            if (a[j].image == a[i].image && a[j].ws_part == a[i].ws_part) {
                 slots_before += pl.m[j].n_ks * pl.m[j].n_bg;
                 ctrs_before += pl.m[j].n_rs;
             }
@@ -897,6 +898,52 @@ hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st) {
     if (early >= 2) return launch_variant<2, 2>(grp, next, st);
     if (early >= 1) return launch_variant<2, 1>(grp, next, st);
     return launch_variant<2, 0>(grp, next, st);
+}
+
+// ---- the entry point that allocates nothing: workspace in a static device array
+// (for callers that cannot call hipMalloc or lend a workspace: code under graph capture, serving
+// loops).  Every device the library runs on holds its own copy until the process ends.  All calls on
+// a device share it: calls that overlap in time on one device race.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<unsigned char*> g_scratch_ptr[kMaxDevices];   // per device: device address of `scratch`
+
+__global__ void k_clear_counters(unsigned* ctr, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) ctr[i] = 0u;
+}
+}  // namespace
+
+hipError_t launch_decode_static(const LaunchArgs& a, hipStream_t st) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    unsigned char* base = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!base) {
+        // first call on this device: the array's name is a host-side stand-in, its device address
+        // comes from the runtime.  The counters must start at zero (the kernels leave them at zero):
+        // cleared once by a small kernel on the caller's stream, ahead of the first launch.
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        base = static_cast<unsigned char*>(ptr);
+        hipLaunchKernelGGL(k_clear_counters, dim3((kCounterSlots + 255) / 256), dim3(256), 0, st,
+                           reinterpret_cast<unsigned*>(base + kStaticPartBytes), kCounterSlots);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev].store(base, std::memory_order_release);
+    }
+    LaunchArgs b = a;
+    b.ws_part = reinterpret_cast<float*>(base);
+    b.ws_ctr = reinterpret_cast<unsigned*>(base + kStaticPartBytes);
+    b.ws_part_slots = int(kStaticPartBytes / (size_t(a.geo.out) * 4));
+    if (b.ws_part_slots < 1) return hipErrorOutOfMemory;
+    DecodePlan pl;
+    if (!plan_decode(&b, 1, &pl)) return hipErrorOutOfMemory;   // no work split fits the array
+    return launch_decode_group(&b, 1, st);
 }
 
 // Estimated duration (microseconds) of one decode launch with m tokens of one stack; 0: the

@@ -393,6 +393,32 @@ int bitstack_linear(const void* x, const bitstack_weight_t* blocks, int n_loaded
     return bitstack_linear_select(x, 1, blocks, n_loaded, y, BITSTACK_Y_F16, BITSTACK_KERNEL_AUTO, stream);
 }
 
+size_t bitstack_static_workspace_bytes(void) { return kStaticScratchBytes; }
+
+int bitstack_linear_static(const void* x, const bitstack_weight_t* blocks, int n_loaded, void* y,
+                           bitstack_stream_t stream) {
+    if (!x || !blocks || !y) return BITSTACK_E_NULL;
+    const Geometry& g = blocks->geo;
+    if (n_loaded < 0 || n_loaded > blocks->resident) return BITSTACK_E_RANGE;
+    if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16) return BITSTACK_E_ALIGN;
+    // the partial rows of even the coarsest work split must fit the static array
+    if (size_t(g.out) * 4 * size_t((g.in / kChunkCols + kDecodeMaxRangeChunks - 1) / kDecodeMaxRangeChunks) > kStaticPartBytes)
+        return BITSTACK_E_BUFSIZE;
+    LaunchArgs a;
+    a.x = x;
+    a.y = y;
+    a.image = blocks->dev;
+    a.geo = g;
+    a.batch = 1;
+    a.n_loaded = n_loaded;
+    a.y_f32 = false;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = n_loaded == 0 ? launch_zero(a, st) : launch_decode_static(a, st);
+    if (e == hipErrorOutOfMemory) return BITSTACK_E_BUFSIZE;
+    if (e != hipSuccess) return hip_fail(e);
+    return BITSTACK_OK;
+}
+
 size_t bitstack_dense_bytes(int out, int in) {
     if (!shape_ok(out, in, kRank)) return 0;
     return size_t(out) * size_t(in) * 2;

@@ -19,6 +19,11 @@ struct LaunchArgs {
     int n_loaded;
     bool y_f32;
     void* wdense = nullptr;  // device fp16 [out][in]: the restored weight of the materialising path
+    // split-accumulation workspace outside the image (the entry point that allocates nothing):
+    // partial rows (ws_part_slots rows of out floats) and arrival counters (kCounterSlots words)
+    float* ws_part = nullptr;
+    unsigned* ws_ctr = nullptr;
+    int ws_part_slots = 0;
 };
 
 // Limits of the decode kernel's work split
@@ -45,6 +50,11 @@ hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st);
 hipError_t launch_decode_group_old(const LaunchArgs* a, int count, hipStream_t st);
 // a.batch tokens through the decode kernel, up to four per launch
 hipError_t launch_decode_tokens(const LaunchArgs& a, hipStream_t st);
+// One token with the split-accumulation workspace in the library's static device array instead of
+// the image's.  hipErrorOutOfMemory: the stack's rows do not fit the array (nothing launched).
+constexpr size_t kStaticPartBytes = size_t(4) << 20;   // partial rows
+constexpr size_t kStaticScratchBytes = kStaticPartBytes + size_t(kCounterSlots) * 4;
+hipError_t launch_decode_static(const LaunchArgs& a, hipStream_t st);
 double decode_tokens_time_us(const Geometry& g, int batch, int n_loaded);
 hipError_t launch_panel(const LaunchArgs& a, hipStream_t st);
 // materialising path: W' diag(1/s) of the loaded prefix -> a.wdense; then y = x wdense^T

@@ -48,10 +48,10 @@ inline KParams make_params(const LaunchArgs& a) {
     p.off_v = a.geo.off_v;
     p.off_u = a.geo.off_u;
     p.vmax = reinterpret_cast<const __half*>(a.image + a.geo.off_vmax);
-    p.part = reinterpret_cast<float*>(a.image + a.geo.off_part);
-    p.part_slots = a.geo.part_slots;
+    p.part = a.ws_part ? a.ws_part : reinterpret_cast<float*>(a.image + a.geo.off_part);
+    p.part_slots = a.ws_part ? a.ws_part_slots : a.geo.part_slots;
     p.n_bg = 1;
-    p.ctr = reinterpret_cast<unsigned*>(a.image + a.geo.off_ctr);
+    p.ctr = a.ws_part ? a.ws_ctr : reinterpret_cast<unsigned*>(a.image + a.geo.off_ctr);
     p.out = a.geo.out;
     p.in = a.geo.in;
     p.batch = a.batch;

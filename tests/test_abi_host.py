@@ -16,10 +16,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "bitstack.h")).read()
-    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(bitstack_[a-z0-9_]+)\s*\(", hdr))
-    assert {"bitstack_linear", "bitstack_pack_blocks", "bitstack_linear_batched"} <= names
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        hdr = open(os.path.join(ROOT, "include", header)).read()
+        hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+        names |= set(re.findall(r"\b(bitstack_[a-z0-9_]+)\s*\(", hdr))
+    assert {"bitstack_linear", "bitstack_pack_blocks", "bitstack_linear_batched", "bitstack_linear_static",
+            "bitstack_set_option", "bitstack_probe_read"} <= names
     L = B.lib()
     for name in sorted(names):
         assert hasattr(L, name), name
