@@ -156,8 +156,6 @@ int bitstack_create_stack(int out, int in, int k, int n_slots, int max_batch, co
  * unchanged until the copies have run.  BITSTACK_E_RANGE when every slot is taken. */
 int bitstack_push_block(bitstack_weight_t* w, const void* staging, bitstack_stream_t stream);
 
-/* Offloads the last loaded block: no device work, its slot is free for the next push.  Calls
- * already enqueued that use the block must have finished before the slot is overwritten. */
 /* The same from canonical arrays that already are in device memory (what bitstack_decompose
  * writes: one block's sign words [out][in/32], U [out][k] 16-byte aligned, V [in][k]): a
  * re-tiling kernel writes the block and its row maxima into the next free slot, no host copy.
@@ -165,6 +163,10 @@ int bitstack_push_block(bitstack_weight_t* w, const void* staging, bitstack_stre
  * Asynchronous; the arrays must stay valid until the stream has passed the call. */
 int bitstack_push_block_device(bitstack_weight_t* w, const uint32_t* sign_words, const uint16_t* U,
                                const uint16_t* V, bitstack_stream_t stream);
+
+/* Offloads the last loaded block: no device work, its slot is free for the next push.  Calls
+ * already enqueued that use the block must have finished before the slot is overwritten.
+ * BITSTACK_E_RANGE when no block is loaded. */
 int bitstack_pop_block(bitstack_weight_t* w);
 
 /* Number of loaded blocks, and their bytes by Eq. (9): resident * bitstack_block_bytes. */

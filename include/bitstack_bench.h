@@ -18,13 +18,11 @@ extern "C" {
  * value the launcher cannot honour makes it fall back to its own choice or refuse
  * the launch with BITSTACK_E_HIP before anything is enqueued. */
 enum {
-    BITSTACK_OPT_DECODE_LEGACY_KSLAB = 2, /* legacy kernel: input columns per workgroup, 256 / 512 / 1024 */
     BITSTACK_OPT_DECODE_BGROUPS = 3,      /* workgroups sharing one (row slab, column range) pair; each
                                              walks every BGROUPS-th block of the loaded prefix (single calls) */
     BITSTACK_OPT_DECODE_TILES = 4,        /* 32-row tiles per wavefront: 2 or 4 (512 / 1024 rows per workgroup) */
     BITSTACK_OPT_DECODE_KS_CHUNKS = 5,    /* 256-column chunks per workgroup: 1..32 */
-    BITSTACK_OPT_DECODE_EARLY = 6,        /* value - 1 = chunks of the first sign window requested at entry: 0, 2, 4 */
-    BITSTACK_OPT_DECODE_LEGACY = 7        /* 1: the producer/consumer kernel kept for comparison */
+    BITSTACK_OPT_DECODE_EARLY = 6         /* value - 1 = chunks of the first sign window requested at entry: 0, 2, 4 */
 };
 int bitstack_set_option(int option, int value);
 

@@ -7,8 +7,7 @@ from .binding import (  # noqa: F401
     BitStackError,
     PackedStack,
     KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL, KERNEL_MATERIALISE,
-    OPT_DECODE_LEGACY_KSLAB, OPT_DECODE_BGROUPS, OPT_DECODE_TILES, OPT_DECODE_KS_CHUNKS, OPT_DECODE_EARLY,
-    OPT_DECODE_LEGACY,
+    OPT_DECODE_BGROUPS, OPT_DECODE_TILES, OPT_DECODE_KS_CHUNKS, OPT_DECODE_EARLY,
     block_bytes,
     block_staging_bytes,
     dense_bytes,

@@ -850,7 +850,6 @@ hipError_t launch_variant(const KGroup& grp, unsigned wgs, hipStream_t st) {
 hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st) {
     if (count < 1 || count > kMaxGroup) return hipErrorInvalidValue;
     const DecodeTuning& tn = decode_tuning();
-    if (tn.legacy.load()) return launch_decode_group_old(a, count, st);
     for (int i = 0; i < count; ++i) {
         if (a[i].batch != 1 || a[i].n_loaded < 1 || a[i].geo.in != a[0].geo.in) return hipErrorInvalidValue;
         const size_t sign_span = size_t(a[i].geo.n) * a[i].geo.block_stride;

@@ -241,7 +241,7 @@ hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {
     if (a.batch < 1 || p.wdense == nullptr) return hipErrorInvalidValue;
     if (size_t(p.batch) * p.in * 2 > 0xffffffffull || size_t(p.out) * p.in * 2 > 0xffffffffull)
         return hipErrorInvalidValue;   // 32-bit byte offsets into x and the dense weight
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // setting the attribute twice is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<4>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);

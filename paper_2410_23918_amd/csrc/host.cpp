@@ -205,7 +205,12 @@ int bitstack_create_stack(int out, int in, int k, int n_slots, int max_batch, co
     if (reinterpret_cast<uintptr_t>(device_buf) % 256) return BITSTACK_E_ALIGN;
     const Geometry g = make_geometry(out, in, n_slots, max_batch);
     if (device_buf_bytes < g.total) return BITSTACK_E_BUFSIZE;
-    std::vector<float> rs(in);
+    std::vector<float> rs;
+    try {
+        rs.resize(in);
+    } catch (const std::bad_alloc&) {
+        return BITSTACK_E_BUFSIZE;
+    }
     for (int j = 0; j < in; ++j) rs[j] = 1.0f / s[j];
     hipStream_t st = static_cast<hipStream_t>(stream);
     unsigned char* dev = static_cast<unsigned char*>(device_buf);
@@ -535,27 +540,26 @@ int bitstack_probe_read(const void* device_buf, size_t bytes, void* device_sink,
 int bitstack_set_option(int option, int value) {
     if (value < 0) return BITSTACK_E_ARG;
     switch (option) {
-        case BITSTACK_OPT_DECODE_LEGACY_KSLAB: decode_tuning().legacy_kslab = value; return BITSTACK_OK;
         case BITSTACK_OPT_DECODE_BGROUPS: decode_tuning().bgroups = value; return BITSTACK_OK;
         case BITSTACK_OPT_DECODE_TILES: decode_tuning().tiles = value; return BITSTACK_OK;
         case BITSTACK_OPT_DECODE_KS_CHUNKS: decode_tuning().ks_chunks = value; return BITSTACK_OK;
         case BITSTACK_OPT_DECODE_EARLY: decode_tuning().early = value - 1; return BITSTACK_OK;
-        case BITSTACK_OPT_DECODE_LEGACY: decode_tuning().legacy = value; return BITSTACK_OK;
         default: return BITSTACK_E_ARG;
     }
 }
 
 // can job j ride in the same decode launch as the jobs [first, j) before it?  Same input
-// vector, same slab width, a non-empty stack, and no output of the group overlapping the input
-// (jobs of one launch run concurrently).
+// vector, non-empty stacks, aligned pointers on both sides, and no output of the group
+// overlapping the input or another output (jobs of one launch run concurrently).
 static bool can_join(const bitstack_job_t* jobs, int first, int j) {
     const bitstack_job_t& a = jobs[first];
     const bitstack_job_t& b = jobs[j];
     if (!a.x || !a.blocks || !a.y || !b.x || !b.blocks || !b.y) return false;
     if (b.x != a.x || b.blocks->geo.in != a.blocks->geo.in) return false;
-    if (b.blocks->geo.min_slab != a.blocks->geo.min_slab) return false;
     if (b.n_loaded < 1 || b.n_loaded > b.blocks->resident || a.n_loaded < 1 || a.n_loaded > a.blocks->resident) return false;
-    if (reinterpret_cast<uintptr_t>(b.x) % 16 || reinterpret_cast<uintptr_t>(b.y) % 16) return false;
+    if (reinterpret_cast<uintptr_t>(a.x) % 16 || reinterpret_cast<uintptr_t>(a.y) % 16 ||
+        reinterpret_cast<uintptr_t>(b.y) % 16)
+        return false;
     const char* x0 = static_cast<const char*>(a.x);
     const char* x1 = x0 + size_t(a.blocks->geo.in) * 2;
     for (int k = first; k <= j; ++k) {
@@ -594,7 +598,17 @@ int bitstack_linear_many(const bitstack_job_t* jobs, int count, int repeat, bits
                     a[k].y_f32 = false;
                 }
                 hipError_t e = launch_decode_group(a, len, st);
-                if (e != hipSuccess) return hip_fail(e);
+                if (e == hipErrorInvalidValue) {
+                    // no joint work split fits the members' workspaces: nothing was enqueued,
+                    // the jobs go out one by one instead
+                    for (int k = 0; k < len; ++k) {
+                        const bitstack_job_t& jb = jobs[i + k];
+                        int rc = bitstack_linear(jb.x, jb.blocks, jb.n_loaded, jb.y, stream);
+                        if (rc) return rc;
+                    }
+                } else if (e != hipSuccess) {
+                    return hip_fail(e);
+                }
             } else {
                 int rc = bitstack_linear(jobs[i].x, jobs[i].blocks, jobs[i].n_loaded, jobs[i].y, stream);
                 if (rc) return rc;

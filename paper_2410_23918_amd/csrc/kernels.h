@@ -37,8 +37,6 @@ struct DecodeTuning {
     std::atomic<int> ks_chunks{0};  // 256-column chunks per workgroup
     std::atomic<int> bgroups{0};    // block groups (workgroups per row slab / column range pair)
     std::atomic<int> early{-1};     // chunks of the first sign window requested before the prologue's arithmetic
-    std::atomic<int> legacy{0};     // 1: the producer/consumer kernel (kernels.hip) instead of decode.hip
-    std::atomic<int> legacy_kslab{0};
 };
 DecodeTuning& decode_tuning();
 
@@ -47,7 +45,6 @@ hipError_t launch_zero(const LaunchArgs& a, hipStream_t st);
 hipError_t launch_reference(const LaunchArgs& a, hipStream_t st);
 // up to 4 batch-1 calls that read the same activation vector in one launch
 hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st);
-hipError_t launch_decode_group_old(const LaunchArgs* a, int count, hipStream_t st);
 // a.batch tokens through the decode kernel, up to four per launch
 hipError_t launch_decode_tokens(const LaunchArgs& a, hipStream_t st);
 // One token with the split-accumulation workspace in the library's static device array instead of

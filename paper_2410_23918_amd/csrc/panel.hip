@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) void k_panel(KParams p) {
 template <int TT>
 static hipError_t launch_panel_t(const KParams& p, hipStream_t st) {
     const size_t smem = size_t(128 + kPanelRows) * kPanelLd * 2 + 2 * 4096 * 2;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // setting the attribute twice is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_panel<TT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(smem));
@@ -526,6 +526,10 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
     //      tiles in a fixed order and stores y (same protocol as the decode kernel: write-through
     //      stores, one relaxed agent-scope counter after a barrier, agent-scope loads by the last one)
     unsigned* const flag = reinterpret_cast<unsigned*>(smem + 32768);
+    // vmcnt(0), other counters left alone: each wavefront's write-through stores above have been
+    // acknowledged before it reaches the barrier, so the counter below is bumped only once every
+    // partial value of this workgroup is visible at agent scope
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     unsigned* const ctr = p.ctr + blockIdx.y * gridDim.x + blockIdx.x;
     if (tid == 0) {
@@ -577,7 +581,7 @@ int small_batch_split(int out, int in, int batch, int part_slots) {
 
 static hipError_t launch_fused(KParams p, hipStream_t st) {
     const size_t smem = size_t(kFusedFixedLds) + size_t(p.n_loaded) * 2048;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // setting the attribute twice is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_fused),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -914,7 +918,7 @@ static bool tile_fits(const KParams& p) { return p.n_loaded <= kTileMaxBlocks &&
 
 static hipError_t launch_tile(const KParams& p, hipStream_t st) {
     const size_t smem = size_t(kTileFixedLds) + size_t(p.n_loaded) * 2048;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // setting the attribute twice is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tile<false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -933,7 +937,7 @@ hipError_t launch_restore(const LaunchArgs& a, hipStream_t st) {
     KParams p = make_params(a);
     if (a.n_loaded < 1 || a.n_loaded > kTileMaxBlocks || p.wdense == nullptr) return hipErrorInvalidValue;
     const size_t smem = size_t(kTileFixedLds) + size_t(p.n_loaded) * 2048;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // setting the attribute twice is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tile<true>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -144,13 +144,6 @@ def test_small_and_ragged_shapes(B, out, inn, n):
                     err = O.relative_error(y1, ref[:1])
                     print(f"{out}x{inn} tiles={tiles} ks_chunks={ksc} bgroups={bg} early={early}: {err:.2e}", flush=True)
                     assert err <= TOL
-    # the producer/consumer kernel kept for comparison
-    B.set_option(B.OPT_DECODE_LEGACY, 1)
-    try:
-        y1 = _run(B, ps, x[:1], n, B.KERNEL_DECODE)
-    finally:
-        B.set_option(B.OPT_DECODE_LEGACY, 0)
-    assert O.relative_error(y1, ref[:1]) <= TOL
 
 
 @pytest.mark.parametrize("out,inn,n", [(1056, 768, 3), (96, 2048, 2)])
