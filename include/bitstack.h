@@ -58,7 +58,7 @@ enum {
     BITSTACK_E_SCALE   = -5, /* an entry of s is not finite or not > 0            */
     BITSTACK_E_BUFSIZE = -6, /* buffer smaller than bitstack_packed_bytes()       */
     BITSTACK_E_HIP     = -7, /* a HIP runtime call failed: bitstack_last_hip_error() */
-    BITSTACK_E_ARG     = -8  /* unknown dtype / kernel selector                   */
+    BITSTACK_E_ARG     = -8  /* unknown dtype / kernel selector, invalid block order */
 };
 
 /* output element types for bitstack_linear_batched */
@@ -173,6 +173,57 @@ int bitstack_pop_block(bitstack_weight_t* w);
 int bitstack_resident_blocks(const bitstack_weight_t* w);
 size_t bitstack_resident_bytes(const bitstack_weight_t* w);
 
+/* ---- Block manager: many stacks under one byte budget (Section 2.2: residual blocks are loaded
+ * or offloaded as the available memory changes; Section 2.3: all blocks of all stacks sit in one
+ * universal stack, level by level -- no stack takes its block i+1 before every stack has its
+ * block i -- and inside a level in order of importance; Eq. 9 is the size of a block).
+ * Host logic over bitstack_push_block / bitstack_pop_block; the importance scores that fix the
+ * order inside a level come from the caller (the paper measures them on calibration data). */
+typedef struct bitstack_manager bitstack_manager_t;
+
+/* Host only.  Is `order` (entry e = index of the stack whose next block is loaded e-th) a valid
+ * universal stack for stacks with slots[s] blocks each?  BITSTACK_E_ARG when some stack would
+ * take block i+1 while another still lacks its block i, BITSTACK_E_RANGE for a stack index out
+ * of range or more entries for a stack than it has blocks.  A prefix of a full order is valid. */
+int bitstack_order_check(int n_stacks, const int* slots, const int* order, int count);
+
+/* Host only.  How far down the universal stack a byte budget reaches: the largest `position`
+ * such that the blocks of entries [0, position) fit, sum of block_bytes[order[e]] <= budget
+ * (loading stops at the first block that does not fit: the order is an order of importance,
+ * nothing is skipped).  *bytes (optional) receives that sum. */
+int bitstack_budget_position(int n_stacks, const size_t* block_bytes, const int* order, int count,
+                             size_t budget, int* position, size_t* bytes);
+
+/* A manager over n_stacks stacks made by bitstack_create_stack, all empty; it keeps the
+ * pointers (the stacks must outlive it and are not released by it). */
+int bitstack_manager_create(int n_stacks, bitstack_weight_t* const* stacks, bitstack_manager_t** handle);
+void bitstack_manager_release(bitstack_manager_t* m);
+
+/* Where block `block` of stack `stack` waits in host memory (a buffer written by
+ * bitstack_stage_block_host, caller-owned, unchanged while the manager lives; pinned memory
+ * makes the copies asynchronous). */
+int bitstack_manager_set_block(bitstack_manager_t* m, int stack, int block, const void* staging);
+
+/* The universal stack (checked with bitstack_order_check against the stacks' slot counts).
+ * Only while nothing is loaded (BITSTACK_E_ARG otherwise). */
+int bitstack_manager_set_order(bitstack_manager_t* m, const int* order, int count);
+
+/* Moves to the position bitstack_budget_position gives for budget_bytes: offloads from the top
+ * of the universal stack (no device work) and/or loads the next entries (host-to-device copies
+ * enqueued on `stream`; forward calls enqueued on that stream afterwards see the new blocks,
+ * and calls enqueued on it earlier have read a popped slot before a later push overwrites it).
+ * Bytes are counted by Eq. 9 exactly: afterwards bitstack_manager_resident_bytes <= budget and
+ * the next entry, if any, does not fit.  *loaded / *offloaded (optional) count the blocks moved.
+ * BITSTACK_E_NULL when a block on the way up has not been given with set_block: nothing moves. */
+int bitstack_manager_set_budget(bitstack_manager_t* m, size_t budget_bytes, bitstack_stream_t stream,
+                                int* loaded, int* offloaded);
+
+/* Entries of the universal stack that are loaded; their bytes by Eq. 9; loaded blocks of one stack
+ * (the n_loaded to pass to the forward calls). */
+int bitstack_manager_position(const bitstack_manager_t* m);
+size_t bitstack_manager_resident_bytes(const bitstack_manager_t* m);
+int bitstack_manager_n_loaded(const bitstack_manager_t* m, int stack);
+
 /* The forward pass for one token (batch-1 decode):
  *   y = ( sum_{i < n_loaded} S_i (.) (U_i V_i^T) ) diag(1/s) x           (Eq. 4 + Eq. 8)
  *   x: device fp16 [in], 16-byte aligned.   y: device fp16 [out], 16-byte aligned.
@@ -198,6 +249,27 @@ typedef struct bitstack_job {
     void* y;                         /* device fp16 [out] */
 } bitstack_job_t;
 int bitstack_linear_many(const bitstack_job_t* jobs, int count, int repeat, bitstack_stream_t stream);
+
+/* A token plan: the job list of bitstack_linear_many prepared once -- which consecutive jobs
+ * share a launch, the work split of every launch, the kernels' argument blocks -- and then
+ * launched once per token with no host work besides the launches themselves (a decoder sends
+ * the same 224 linears through the library for every token; only the contents of the x and y
+ * buffers change, Section 2.2's n_loaded per matrix stays until the memory budget moves).
+ *   create: checks every job as bitstack_linear would (null pointers, n_loaded against the
+ *           loaded blocks, alignment), enqueues nothing.  The plan keeps the pointers of the
+ *           jobs (x, y, stacks), not the job array itself.
+ *   launch: enqueues the plan's launches on `stream`.  Same bits in every y as
+ *           bitstack_linear_many(jobs, count, 1, stream) gives for the same buffers.
+ *           BITSTACK_E_RANGE if a stack now holds fewer blocks than its job uses: make a new
+ *           plan after the budget has moved.
+ *   steps:  number of kernel launches per bitstack_plan_launch.
+ * A plan may be launched any number of times, also into a HIP graph capture (it allocates
+ * nothing and records kernels only); it is not tied to a stream. */
+typedef struct bitstack_plan bitstack_plan_t;
+int bitstack_plan_create(const bitstack_job_t* jobs, int count, bitstack_plan_t** handle);
+int bitstack_plan_launch(const bitstack_plan_t* plan, bitstack_stream_t stream);
+int bitstack_plan_steps(const bitstack_plan_t* plan);
+void bitstack_plan_release(bitstack_plan_t* plan);
 
 /* Same for a batch of tokens.  x: device fp16 [batch][in] row-major;
  * y: device [batch][out] row-major of y_dtype (BITSTACK_Y_F16 / BITSTACK_Y_F32);

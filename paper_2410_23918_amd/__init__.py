@@ -6,6 +6,10 @@ marshals arguments.  PyTorch supplies device memory and streams.
 from .binding import (  # noqa: F401
     BitStackError,
     PackedStack,
+    BlockManager,
+    TokenPlan,
+    order_check,
+    budget_position,
     KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL, KERNEL_MATERIALISE,
     OPT_DECODE_BGROUPS, OPT_DECODE_TILES, OPT_DECODE_KS_CHUNKS, OPT_DECODE_EARLY,
     block_bytes,

@@ -95,6 +95,34 @@ def lib():
     L.bitstack_decompose_workspace_bytes.argtypes = [i32, i32, i32]
     L.bitstack_decompose.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
     L.bitstack_decompose.restype = i32
+    L.bitstack_order_check.argtypes = [i32, vp, vp, i32]
+    L.bitstack_order_check.restype = i32
+    L.bitstack_budget_position.argtypes = [i32, vp, vp, i32, sz, C.POINTER(i32), C.POINTER(sz)]
+    L.bitstack_budget_position.restype = i32
+    L.bitstack_manager_create.argtypes = [i32, vp, C.POINTER(vp)]
+    L.bitstack_manager_create.restype = i32
+    L.bitstack_manager_release.argtypes = [vp]
+    L.bitstack_manager_release.restype = None
+    L.bitstack_manager_set_block.argtypes = [vp, i32, i32, vp]
+    L.bitstack_manager_set_block.restype = i32
+    L.bitstack_manager_set_order.argtypes = [vp, vp, i32]
+    L.bitstack_manager_set_order.restype = i32
+    L.bitstack_manager_set_budget.argtypes = [vp, sz, vp, C.POINTER(i32), C.POINTER(i32)]
+    L.bitstack_manager_set_budget.restype = i32
+    L.bitstack_manager_position.argtypes = [vp]
+    L.bitstack_manager_position.restype = i32
+    L.bitstack_manager_resident_bytes.argtypes = [vp]
+    L.bitstack_manager_resident_bytes.restype = sz
+    L.bitstack_manager_n_loaded.argtypes = [vp, i32]
+    L.bitstack_manager_n_loaded.restype = i32
+    L.bitstack_plan_create.argtypes = [vp, i32, C.POINTER(vp)]
+    L.bitstack_plan_create.restype = i32
+    L.bitstack_plan_launch.argtypes = [vp, vp]
+    L.bitstack_plan_launch.restype = i32
+    L.bitstack_plan_steps.argtypes = [vp]
+    L.bitstack_plan_steps.restype = i32
+    L.bitstack_plan_release.argtypes = [vp]
+    L.bitstack_plan_release.restype = None
     L.bitstack_release.argtypes = [vp]
     L.bitstack_release.restype = None
     L.bitstack_strerror.restype = C.c_char_p
@@ -128,6 +156,35 @@ def linear_many(jobs, repeat: int = 1, stream=None):
     import torch
     st = C.c_void_p((stream or torch.cuda.current_stream()).cuda_stream)
     _check(lib().bitstack_linear_many(jobs, len(jobs), repeat, st), "bitstack_linear_many")
+
+
+class TokenPlan:
+    """bitstack_plan_*: a job array from make_jobs prepared once, launched once per token."""
+
+    def __init__(self, jobs):
+        self._jobs = jobs   # keeps the tensors and stacks alive
+        self._h = C.c_void_p()
+        _check(lib().bitstack_plan_create(jobs, len(jobs), C.byref(self._h)), "bitstack_plan_create")
+
+    @property
+    def steps(self) -> int:
+        return int(lib().bitstack_plan_steps(self._h))
+
+    def launch(self, stream=None):
+        import torch
+        st = C.c_void_p((stream or torch.cuda.current_stream()).cuda_stream)
+        _check(lib().bitstack_plan_launch(self._h, st), "bitstack_plan_launch")
+
+    def release(self):
+        if self._h:
+            lib().bitstack_plan_release(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.release()
+        except Exception:
+            pass
 
 
 def _check(rc: int, where: str):
@@ -226,6 +283,76 @@ def decompose(W, s, n: int, k: int = 16, iterations: int = 0, stream=None):
            "bitstack_decompose")
     stream.synchronize()   # the workspace is released when this function returns
     return sw, U, V
+
+
+def order_check(slots, order) -> int:
+    """bitstack_order_check (host only): 0 if `order` is a valid universal stack, else the error code."""
+    sl = np.ascontiguousarray(slots, dtype=np.int32)
+    od = np.ascontiguousarray(order, dtype=np.int32)
+    return int(lib().bitstack_order_check(len(sl), _ptr(sl), _ptr(od), len(od)))
+
+
+def budget_position(block_bytes_per_stack, order, budget: int):
+    """bitstack_budget_position (host only) -> (position, bytes)."""
+    bb = np.ascontiguousarray(block_bytes_per_stack, dtype=np.uint64)
+    od = np.ascontiguousarray(order, dtype=np.int32)
+    pos, tot = C.c_int(), C.c_size_t()
+    _check(lib().bitstack_budget_position(len(bb), _ptr(bb), _ptr(od), len(od), int(budget), C.byref(pos), C.byref(tot)),
+           "bitstack_budget_position")
+    return pos.value, tot.value
+
+
+class BlockManager:
+    """bitstack_manager_*: empty stacks (PackedStack.empty), their blocks staged in pinned host
+    memory, a universal stack, a byte budget."""
+
+    def __init__(self, stacks):
+        self.stacks = list(stacks)
+        arr = (C.c_void_p * len(self.stacks))(*[ps.handle.value for ps in self.stacks])
+        self._h = C.c_void_p()
+        self._pinned = []
+        _check(lib().bitstack_manager_create(len(self.stacks), arr, C.byref(self._h)), "bitstack_manager_create")
+
+    def stage_block(self, stack: int, block: int, sign_words, U, V):
+        import torch
+        ps = self.stacks[stack]
+        pinned = torch.empty(block_staging_bytes(ps.out, ps.inn, ps.k), dtype=torch.uint8, pin_memory=True)
+        stage_block_host(sign_words, U, V, pinned.numpy())
+        self._pinned.append(pinned)
+        _check(lib().bitstack_manager_set_block(self._h, stack, block, pinned.data_ptr()), "bitstack_manager_set_block")
+
+    def set_order(self, order):
+        od = np.ascontiguousarray(order, dtype=np.int32)
+        _check(lib().bitstack_manager_set_order(self._h, _ptr(od), len(od)), "bitstack_manager_set_order")
+
+    def set_budget(self, budget: int, stream=None):
+        """-> (blocks loaded, blocks offloaded)"""
+        up, down = C.c_int(), C.c_int()
+        _check(lib().bitstack_manager_set_budget(self._h, int(budget), self.stacks[0]._stream(stream), C.byref(up),
+                                                 C.byref(down)), "bitstack_manager_set_budget")
+        return up.value, down.value
+
+    @property
+    def position(self) -> int:
+        return int(lib().bitstack_manager_position(self._h))
+
+    @property
+    def resident_bytes(self) -> int:
+        return int(lib().bitstack_manager_resident_bytes(self._h))
+
+    def n_loaded(self, stack: int) -> int:
+        return int(lib().bitstack_manager_n_loaded(self._h, stack))
+
+    def release(self):
+        if self._h:
+            lib().bitstack_manager_release(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.release()
+        except Exception:
+            pass
 
 
 def restore_max_blocks() -> int:

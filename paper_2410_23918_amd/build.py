@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbitstack.so")
-SOURCES = ["host.cpp", "kernels.hip", "decode.hip", "panel.hip", "dense.hip", "decompose.hip"]
+SOURCES = ["host.cpp", "manager.cpp", "kernels.hip", "decode.hip", "panel.hip", "dense.hip", "decompose.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-munsafe-fp-atomics",

@@ -848,6 +848,13 @@ hipError_t launch_variant(const KGroup& grp, unsigned wgs, hipStream_t st) {
 }  // namespace
 
 hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st) {
+    DecodeLaunch d;
+    const hipError_t e = prepare_decode_group(a, count, &d);
+    return e != hipSuccess ? e : run_decode_launch(d, st);
+}
+
+// Work split and argument block of one launch (host only, nothing is enqueued).
+hipError_t prepare_decode_group(const LaunchArgs* a, int count, DecodeLaunch* d) {
     if (count < 1 || count > kMaxGroup) return hipErrorInvalidValue;
     const DecodeTuning& tn = decode_tuning();
     for (int i = 0; i < count; ++i) {
@@ -857,7 +864,7 @@ hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st) {
     }
     DecodePlan pl;
     if (!plan_decode(a, count, &pl)) return hipErrorInvalidValue;   // nothing has been launched
-    KGroup grp;
+    KGroup& grp = d->grp;
     grp.count = count;
     unsigned next = 0;
     for (int i = 0; i < count; ++i) {
@@ -887,7 +894,17 @@ hipError_t launch_decode_group(const LaunchArgs* a, int count, hipStream_t st) {
     for (int i = count; i <= kMaxGroup; ++i) grp.base[i] = next;
     int early = tn.early.load();
     if (early < 0) early = 2;
-    if (pl.tiles == 4) {
+    d->wgs = next;
+    d->tiles = pl.tiles;
+    d->early = early;
+    return hipSuccess;
+}
+
+hipError_t run_decode_launch(const DecodeLaunch& d, hipStream_t st) {
+    const KGroup& grp = d.grp;
+    const unsigned next = d.wgs;
+    const int early = d.early;
+    if (d.tiles == 4) {
         if (early >= 4) return launch_variant<4, 4>(grp, next, st);
         if (early >= 2) return launch_variant<4, 2>(grp, next, st);
         if (early >= 1) return launch_variant<4, 1>(grp, next, st);

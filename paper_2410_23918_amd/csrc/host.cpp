@@ -576,6 +576,32 @@ static bool can_join(const bitstack_job_t* jobs, int first, int j) {
     return true;
 }
 
+static LaunchArgs job_args(const bitstack_job_t& jb) {
+    LaunchArgs a;
+    a.x = jb.x;
+    a.y = jb.y;
+    a.image = jb.blocks->dev;
+    a.geo = jb.blocks->geo;
+    a.batch = 1;
+    a.n_loaded = jb.n_loaded;
+    a.y_f32 = false;
+    return a;
+}
+
+// length of the run of jobs starting at i that go out as one decode launch (1: a call of its own)
+static int group_length(const bitstack_job_t* jobs, int count, int i) {
+    int len = 1;
+    while (i + len < count && len < kMaxGroup && can_join(jobs, i, i + len)) ++len;
+    if (len > 1) {
+        // a joint work split must fit the members' workspaces; else the jobs go out one by one
+        LaunchArgs a[kMaxGroup];
+        for (int k = 0; k < len; ++k) a[k] = job_args(jobs[i + k]);
+        DecodeLaunch d;
+        if (prepare_decode_group(a, len, &d) != hipSuccess) len = 1;
+    }
+    return len;
+}
+
 int bitstack_linear_many(const bitstack_job_t* jobs, int count, int repeat, bitstack_stream_t stream) {
     if (!jobs) return BITSTACK_E_NULL;
     if (count < 0 || repeat < 0) return BITSTACK_E_RANGE;
@@ -583,32 +609,12 @@ int bitstack_linear_many(const bitstack_job_t* jobs, int count, int repeat, bits
     for (int r = 0; r < repeat; ++r) {
         int i = 0;
         while (i < count) {
-            int len = 1;
-            while (i + len < count && len < kMaxGroup && can_join(jobs, i, i + len)) ++len;
+            const int len = group_length(jobs, count, i);
             if (len > 1) {
                 LaunchArgs a[kMaxGroup];
-                for (int k = 0; k < len; ++k) {
-                    const bitstack_job_t& jb = jobs[i + k];
-                    a[k].x = jb.x;
-                    a[k].y = jb.y;
-                    a[k].image = jb.blocks->dev;
-                    a[k].geo = jb.blocks->geo;
-                    a[k].batch = 1;
-                    a[k].n_loaded = jb.n_loaded;
-                    a[k].y_f32 = false;
-                }
+                for (int k = 0; k < len; ++k) a[k] = job_args(jobs[i + k]);
                 hipError_t e = launch_decode_group(a, len, st);
-                if (e == hipErrorInvalidValue) {
-                    // no joint work split fits the members' workspaces: nothing was enqueued,
-                    // the jobs go out one by one instead
-                    for (int k = 0; k < len; ++k) {
-                        const bitstack_job_t& jb = jobs[i + k];
-                        int rc = bitstack_linear(jb.x, jb.blocks, jb.n_loaded, jb.y, stream);
-                        if (rc) return rc;
-                    }
-                } else if (e != hipSuccess) {
-                    return hip_fail(e);
-                }
+                if (e != hipSuccess) return hip_fail(e);
             } else {
                 int rc = bitstack_linear(jobs[i].x, jobs[i].blocks, jobs[i].n_loaded, jobs[i].y, stream);
                 if (rc) return rc;
@@ -618,6 +624,76 @@ int bitstack_linear_many(const bitstack_job_t* jobs, int count, int repeat, bits
     }
     return BITSTACK_OK;
 }
+
+// ---- a token plan: the job list of bitstack_linear_many with grouping, work splits and kernel
+// arguments worked out once
+struct bitstack_plan {
+    struct Step {
+        bool zero;        // y = 0 (no block loaded)
+        LaunchArgs za;    // for zero
+        DecodeLaunch d;   // else
+    };
+    std::vector<Step> steps;
+    std::vector<bitstack_job_t> jobs;   // kept to check at launch that the stacks still hold the blocks
+};
+
+int bitstack_plan_create(const bitstack_job_t* jobs, int count, bitstack_plan_t** handle) {
+    if (!handle) return BITSTACK_E_NULL;
+    *handle = nullptr;
+    if (!jobs) return BITSTACK_E_NULL;
+    if (count < 0) return BITSTACK_E_RANGE;
+    for (int i = 0; i < count; ++i) {   // the checks of bitstack_linear, for every job, before anything is built
+        const bitstack_job_t& jb = jobs[i];
+        if (!jb.x || !jb.blocks || !jb.y) return BITSTACK_E_NULL;
+        if (jb.n_loaded < 0 || jb.n_loaded > jb.blocks->resident) return BITSTACK_E_RANGE;
+        if (reinterpret_cast<uintptr_t>(jb.x) % 16 || reinterpret_cast<uintptr_t>(jb.y) % 16) return BITSTACK_E_ALIGN;
+    }
+    bitstack_plan* pl = new (std::nothrow) bitstack_plan;
+    if (!pl) return BITSTACK_E_BUFSIZE;
+    try {
+        pl->jobs.assign(jobs, jobs + count);
+        int i = 0;
+        while (i < count) {
+            const int len = group_length(jobs, count, i);
+            pl->steps.emplace_back();
+            bitstack_plan::Step& s = pl->steps.back();
+            LaunchArgs a[kMaxGroup];
+            for (int k = 0; k < len; ++k) a[k] = job_args(jobs[i + k]);
+            s.zero = len == 1 && jobs[i].n_loaded == 0;
+            if (s.zero) {
+                s.za = a[0];
+            } else {
+                const hipError_t e = prepare_decode_group(a, len, &s.d);
+                if (e != hipSuccess) {
+                    delete pl;
+                    return hip_fail(e);
+                }
+            }
+            i += len;
+        }
+    } catch (const std::bad_alloc&) {
+        delete pl;
+        return BITSTACK_E_BUFSIZE;
+    }
+    *handle = pl;
+    return BITSTACK_OK;
+}
+
+int bitstack_plan_launch(const bitstack_plan_t* plan, bitstack_stream_t stream) {
+    if (!plan) return BITSTACK_E_NULL;
+    for (const bitstack_job_t& jb : plan->jobs)
+        if (jb.n_loaded > jb.blocks->resident) return BITSTACK_E_RANGE;   // a block of the plan has been offloaded
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    for (const bitstack_plan::Step& s : plan->steps) {
+        const hipError_t e = s.zero ? launch_zero(s.za, st) : run_decode_launch(s.d, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return BITSTACK_OK;
+}
+
+int bitstack_plan_steps(const bitstack_plan_t* plan) { return plan ? int(plan->steps.size()) : BITSTACK_E_NULL; }
+
+void bitstack_plan_release(bitstack_plan_t* plan) { delete plan; }
 
 void bitstack_release(bitstack_weight_t* w) { delete w; }
 

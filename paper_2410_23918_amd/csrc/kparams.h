@@ -38,6 +38,16 @@ struct KGroup {
     int count;
 };
 
+// One decode launch, fully prepared: the kernel's argument block, its grid and the variant
+// (tiles per wavefront, chunks of the first window requested early).  Made once, launched many times.
+struct DecodeLaunch {
+    KGroup grp;
+    unsigned wgs;
+    int tiles, early;
+};
+hipError_t prepare_decode_group(const LaunchArgs* a, int count, DecodeLaunch* d);
+hipError_t run_decode_launch(const DecodeLaunch& d, hipStream_t st);
+
 inline KParams make_params(const LaunchArgs& a) {
     KParams p;
     p.x = static_cast<const __half*>(a.x);
