@@ -235,6 +235,18 @@ def batch_table(B, torch, dev, n):
                     f"max |difference| to the batch kernel / max |y| = {diff:.1e}")
                 rows.append({"shape": f"{o}x{i}", "tokens": b, "kernel": "restore + k_gemm", "us": round(um, 1),
                              "restore_us": round(ur, 1), "useful_TFLOPs": round(tfm, 2)})
+                if b >= 512:
+                    # the same through a scratch of 128 MiB (a slab of rows at a time, the scratch stays in
+                    # the last-level cache): what a caller gets who lends one small buffer for all stacks
+                    slab = wd.view(-1)[: (128 << 20) // 2]
+                    y3 = torch.empty_like(y)
+                    usl = timed(lambda: ps.linear_materialised(x, n, slab, y=y3), 3)
+                    tfs = 2.0 * o * i * b / usl / 1e6
+                    same = bool(torch.equal(y3, y2))
+                    log(f"[bench] materialising path in row slabs, 128 MiB scratch, {o}x{i} n={n} tokens={b}: "
+                        f"{usl:.1f} us, {tfs:.1f} useful TFLOP/s; same bits as with the full scratch: {same}")
+                    rows.append({"shape": f"{o}x{i}", "tokens": b, "kernel": "restore + k_gemm in row slabs, 128 MiB scratch",
+                                 "us": round(usl, 1), "useful_TFLOPs": round(tfs, 2), "same_bits_as_full_scratch": same})
         del ps, wd
     return rows
 

@@ -298,15 +298,20 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* bl
  *   time (BITSTACK_E_RANGE otherwise); x and w_dense below 4 GiB each.
  *   w_dense must hold what bitstack_restore_weight wrote for a stack of the same shape.
  * bitstack_linear_materialised is the two in sequence on one stream; all arguments are checked
- *   before anything is enqueued.
+ *   before anything is enqueued.  Its scratch may be smaller than the whole matrix: with room for
+ *   R rows (R a multiple of 256, at least 1024; BITSTACK_E_BUFSIZE below that) the weight is
+ *   restored and multiplied in slabs of R rows, one after the other through the same scratch --
+ *   same results, a few launches more, and a scratch that stays inside the last-level cache
+ *   when it is a few tens of MB.
  * All three are asynchronous and allocate nothing. */
 size_t bitstack_dense_bytes(int out, int in);
 int bitstack_restore_max_blocks(void);
 
 /* bitstack_linear_batched with an optional scratch buffer (device, caller-owned, 256-byte
- * aligned, may be NULL): when it holds at least bitstack_dense_bytes(out, in) bytes and the
- * materialising path is estimated to be faster for this batch and stack height, that path is
- * taken and overwrites the buffer; otherwise the buffer is left alone.  Same results contract and errors as bitstack_linear_batched.
+ * aligned, may be NULL): when it holds at least 1024 rows of the dense weight (1024 x in x 2
+ * bytes; the whole matrix, bitstack_dense_bytes(out, in), avoids slabs) and the materialising
+ * path is estimated to be faster for this batch and stack height, that path is taken and
+ * overwrites the buffer; otherwise the buffer is left alone.  Same results contract and errors as bitstack_linear_batched.
  * bitstack_choose_kernel (host only, no device work) returns the BITSTACK_KERNEL_* value that
  * call would pick for a stack of this shape (BITSTACK_KERNEL_AUTO for n_loaded = 0, where y is
  * only cleared), or a negative error code for an unsupported shape / out-of-range arguments. */

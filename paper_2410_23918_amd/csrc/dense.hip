@@ -183,7 +183,7 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
                 for (int v = 0; v < 16; ++v) {
                     const int tok = tok0 + tg * 64 + t * 32 + 8 * (v >> 2) + 4 * hl + (v & 3);
                     const int row = row0 + rg * (32 * RJ) + j * 32 + ln;
-                    if (tok < p.batch && row < p.out) static_cast<float*>(p.y)[size_t(tok) * p.out + row] = acc[j][t][v];
+                    if (tok < p.batch && row < p.out) static_cast<float*>(p.y)[size_t(tok) * p.y_ld + row] = acc[j][t][v];
                 }
         return;
     }
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
         const int idx = tid + 512 * k, tok = idx / PIECES, piece = idx % PIECES;
         const uint4 v = *reinterpret_cast<const uint4*>(yl + tok * kGemmYLd + piece * 8);
         if (tok0 + tok < p.batch && row0 + piece * 8 < p.out)
-            *reinterpret_cast<uint4*>(y + size_t(tok0 + tok) * p.out + row0 + piece * 8) = v;
+            *reinterpret_cast<uint4*>(y + size_t(tok0 + tok) * p.y_ld + row0 + piece * 8) = v;
     }
 }
 
@@ -239,6 +239,13 @@ double dense_time_us(int out, int in, int batch) {
 hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {
     KParams p = make_params(a);
     if (a.batch < 1 || p.wdense == nullptr) return hipErrorInvalidValue;
+    if (a.rows) {
+        // a slab of rows: the dense matrix holds rows [row_begin, row_begin + rows) of the weight, the
+        // outputs go to the same columns of y (whose token rows stay the stack's full width apart)
+        if (a.row_begin % 256 || a.row_begin < 0 || a.row_begin >= a.geo.out) return hipErrorInvalidValue;
+        p.out = a.rows < a.geo.out - a.row_begin ? a.rows : a.geo.out - a.row_begin;
+        p.y = static_cast<unsigned char*>(p.y) + size_t(a.row_begin) * (a.y_f32 ? 4 : 2);
+    }
     if (size_t(p.batch) * p.in * 2 > 0xffffffffull || size_t(p.out) * p.in * 2 > 0xffffffffull)
         return hipErrorInvalidValue;   // 32-bit byte offsets into x and the dense weight
     static std::atomic<bool> attr_set{false};   // setting the attribute twice is harmless

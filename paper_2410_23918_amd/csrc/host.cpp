@@ -303,6 +303,16 @@ int bitstack_weight_shape(const bitstack_weight_t* w, int* out, int* in, int* k,
 // launch streams the blocks once per token; the batch path rebuilds signed tiles per group of 32
 // tokens (up to 64 tokens) or a weight tile once per 512 tokens; with a scratch buffer for the
 // dense weight, restoring it once and one dense product wins for prefill-sized batches.
+// Rows of the weight a scratch buffer of this size holds at a time on the materialising path
+// (multiples of 256, the dense kernel's tile height; the whole matrix if it fits; 0: too small to
+// be worth it -- below 1024 rows the dense product no longer fills the chip).
+static int slab_rows(const Geometry& g, size_t workspace_bytes) {
+    const size_t fit = workspace_bytes / (size_t(g.in) * 2);
+    if (fit >= size_t(g.out)) return g.out;
+    const int rows = int(fit / 256) * 256;
+    return rows >= 1024 ? rows : 0;
+}
+
 static int choose_kernel(const Geometry& g, int batch, int n_loaded, size_t workspace_bytes) {
     if (batch == 1) return BITSTACK_KERNEL_DECODE;
     const double t_decode = decode_tokens_time_us(g, batch, n_loaded);   // up to four tokens per launch
@@ -318,9 +328,14 @@ static int choose_kernel(const Geometry& g, int batch, int n_loaded, size_t work
     }
     int kernel = t_decode <= t_panel ? BITSTACK_KERNEL_DECODE : BITSTACK_KERNEL_PANEL;
     const double t_best = t_decode <= t_panel ? t_decode : t_panel;
-    if (n_loaded <= restore_max_blocks() && workspace_bytes >= size_t(g.out) * size_t(g.in) * 2) {
-        // restore (~6.1 T weight-element-blocks/s) + product, ~10 us fixed each
-        const double t_mat = 10.0 + double(g.out) * g.in * n_loaded / 6.1e6 + 10.0 + dense_time_us(g.out, g.in, batch);
+    const int slab = slab_rows(g, workspace_bytes);
+    if (n_loaded <= restore_max_blocks() && slab > 0) {
+        // per slab of rows: restore (~6.1 T weight-element-blocks/s) + product, ~10 us fixed each
+        double t_mat = 0.0;
+        for (int r0 = 0; r0 < g.out; r0 += slab) {
+            const int rows = slab < g.out - r0 ? slab : g.out - r0;
+            t_mat += 10.0 + double(rows) * g.in * n_loaded / 6.1e6 + 10.0 + dense_time_us(rows, g.in, batch);
+        }
         if (t_mat < t_best) kernel = BITSTACK_KERNEL_MATERIALISE;
     }
     return kernel;
@@ -485,17 +500,45 @@ int bitstack_linear_materialised(const void* x, int batch, const bitstack_weight
                                  void* w_dense, size_t w_dense_bytes, void* y, int y_dtype,
                                  bitstack_stream_t stream) {
     if (!x || !y) return BITSTACK_E_NULL;
-    int rc = dense_args(w, w_dense, w_dense_bytes, true);
+    int rc = dense_args(w, w_dense, w_dense_bytes, false);
     if (rc) return rc;
     // every argument is checked before anything is enqueued
     const Geometry& g = w->geo;
+    const int slab = slab_rows(g, w_dense_bytes);
+    if (slab == 0) return BITSTACK_E_BUFSIZE;
     if (n_loaded < 0 || n_loaded > w->resident || n_loaded > restore_max_blocks()) return BITSTACK_E_RANGE;
     if (batch < 1 || batch > g.max_batch) return BITSTACK_E_RANGE;
     if (y_dtype != BITSTACK_Y_F16 && y_dtype != BITSTACK_Y_F32) return BITSTACK_E_ARG;
     if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16) return BITSTACK_E_ALIGN;
-    rc = bitstack_restore_weight(w, n_loaded, w_dense, w_dense_bytes, stream);
-    if (rc) return rc;
-    return bitstack_linear_dense(x, batch, w, w_dense, y, y_dtype, stream);
+    if (slab >= g.out) {
+        rc = bitstack_restore_weight(w, n_loaded, w_dense, w_dense_bytes, stream);
+        if (rc) return rc;
+        return bitstack_linear_dense(x, batch, w, w_dense, y, y_dtype, stream);
+    }
+    // the scratch holds a slab of rows at a time: restore it, multiply it, next slab (stream order
+    // keeps a slab's product ahead of the next restore that overwrites the scratch)
+    LaunchArgs a;
+    a.x = x;
+    a.y = y;
+    a.image = w->dev;
+    a.geo = g;
+    a.batch = batch;
+    a.n_loaded = n_loaded;
+    a.y_f32 = (y_dtype == BITSTACK_Y_F32);
+    a.wdense = w_dense;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (n_loaded == 0) {
+        hipError_t e = launch_zero(a, st);
+        return e == hipSuccess ? BITSTACK_OK : hip_fail(e);
+    }
+    for (int r0 = 0; r0 < g.out; r0 += slab) {
+        a.row_begin = r0;
+        a.rows = slab;
+        hipError_t e = launch_restore(a, st);
+        if (e == hipSuccess) e = launch_dense(a, st);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return BITSTACK_OK;
 }
 
 size_t bitstack_decompose_workspace_bytes(int out, int in, int k) {

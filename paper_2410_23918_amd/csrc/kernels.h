@@ -24,6 +24,9 @@ struct LaunchArgs {
     float* ws_part = nullptr;
     unsigned* ws_ctr = nullptr;
     int ws_part_slots = 0;
+    // materialising path in row slabs: rows [row_begin, row_begin + rows) only (rows = 0: all);
+    // wdense then holds that slab, row-major [rows][in]; both are multiples of 256
+    int row_begin = 0, rows = 0;
 };
 
 // Limits of the decode kernel's work split

@@ -26,6 +26,8 @@ struct KParams {
     int y_f32;
     __half* xpack;        // activation scratch in fragment order (null if the image has none)
     void* wdense;         // fp16 [out][in]: restored weight (materialising path only)
+    int row_begin;        // materialising path in row slabs: first row of the slab wdense holds
+    int y_ld;             // elements between two token rows of y (the stack's out, also when p.out is a slab's)
 };
 
 // Several decode calls that read the same activation vector, merged into one launch: workgroup
@@ -71,6 +73,8 @@ inline KParams make_params(const LaunchArgs& a) {
     p.y_f32 = a.y_f32 ? 1 : 0;
     p.xpack = a.geo.xpack_bytes ? reinterpret_cast<__half*>(a.image + a.geo.off_xpack) : nullptr;
     p.wdense = a.wdense;
+    p.row_begin = a.row_begin;
+    p.y_ld = a.geo.out;
     return p;
 }
 

@@ -655,7 +655,7 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
     const int it_end = min(iters, it_first + its_per_wg);
     if (it_first >= it_end) return;
     const int total = (it_end - it_first) * n;
-    const int rt0 = blockIdx.x * 2, nrt = p.out / kTileRows;
+    const int rt0 = blockIdx.x * 2 + (kRestore ? p.row_begin / kTileRows : 0), nrt = p.out / kTileRows;
     const int rtc[2] = {min(rt0, nrt - 1), min(rt0 + 1, nrt - 1)};   // clamped for loads
     const int tok_w = kRestore ? 0 : blockIdx.y * kTileTokens + wave * 64;   // my first token in the product stage
 
@@ -809,7 +809,7 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
                 const int tm = idx >> 11, r = (idx >> 5) & 63, piece = idx & 31;
                 const int chc = 2 * it + tm, row = (rt0 + (r >> 5)) * kTileRows + (r & 31);
                 if (chc < nch && row < p.out)
-                    *reinterpret_cast<uint4*>(wd + size_t(row) * p.in + chc * kChunkCols + piece * 8) =
+                    *reinterpret_cast<uint4*>(wd + size_t(row - p.row_begin) * p.in + chc * kChunkCols + piece * 8) =
                         *reinterpret_cast<const uint4*>(wt + (tm * kPanelRows + r) * kPanelLd + piece * 8);
             }
         } else if (tok_w < p.batch) {
@@ -949,7 +949,9 @@ hipError_t launch_restore(const LaunchArgs& a, hipStream_t st) {
     // rows, first loads, ~3 us) less often, many short ones fill the last round of the 256
     // compute units better.  Per chunk pair: ~0.9 us per block plus ~2.5 us for the flush.
     const int iters = (p.in / kChunkCols + 1) / 2;
-    const int row_wgs = (p.out + 2 * kTileRows - 1) / (2 * kTileRows);
+    const int slab_rows = a.rows ? a.rows : p.out;
+    if (a.row_begin % 256 || a.row_begin < 0 || a.row_begin >= p.out || slab_rows < 1) return hipErrorInvalidValue;
+    const int row_wgs = (min(slab_rows, p.out - a.row_begin) + 2 * kTileRows - 1) / (2 * kTileRows);
     int slices = 1;
     double best = 0.0;
     for (int sl = 1; sl <= iters; sl *= 2) {

@@ -707,6 +707,46 @@ def test_library_choice_with_an_optional_scratch_buffer(B):
                                     B.KERNEL_MATERIALISE, None) == -8
 
 
+def test_materialised_path_in_row_slabs_through_a_small_scratch(B):
+    """A scratch with room for fewer rows than the weight has: the weight is restored and multiplied
+    slab by slab through it.  Same bits as with a scratch for the whole matrix (the same kernels
+    do the same arithmetic per row), for a slab count that leaves a short last slab, both output
+    types, and through the library's own choice; a scratch below 1024 rows is refused."""
+    import torch
+    out, inn, n = 2336, 1024, 3       # 2336 = 2 x 1024 + 288: two full slabs and a ragged one
+    st = synth_stack(3, out, inn, n)
+    ps = _pack(B, st, max_batch=600)
+    x = acts(3, 600, inn)
+    ref = O.forward_dense(st, x, n)
+    full = torch.empty((out, inn), dtype=torch.float16, device="cuda:0")
+    for rows in (1024, 1280, 2304):
+        slab = torch.full((rows * inn + 100,), 7.0, dtype=torch.float16, device="cuda:0")[: rows * inn + 60]
+        for b in (70, 600):
+            xd = _to_dev(x[:b])
+            for dt in (torch.float16, torch.float32):
+                y_full = ps.linear_materialised(xd, n, full, out_dtype=dt)
+                y_slab = ps.linear_materialised(xd, n, slab, out_dtype=dt)
+                torch.cuda.synchronize()
+                assert torch.equal(y_full, y_slab), (rows, b, dt)
+                err = O.relative_error(y_slab.float().cpu().numpy(), ref[:b])
+                print(f"{out}x{inn} scratch of {rows} rows, B={b} {dt}: {err:.2e}", flush=True)
+                assert err <= TOL
+        assert bool((slab[rows * inn:] == 7.0).all())      # nothing written past the rows that fit
+    slab = torch.empty((1024 * inn,), dtype=torch.float16, device="cuda:0")
+    y0 = ps.linear_materialised(_to_dev(x[:70]), 0, slab)
+    torch.cuda.synchronize()
+    assert not y0.any()
+    # the library's choice takes the slab path for a prefill-sized batch and gives the same result
+    assert B.choose_kernel(out, inn, n, 600, 600, n, slab.numel() * 2) in (B.KERNEL_MATERIALISE, B.KERNEL_PANEL)
+    y = ps.linear_batched_ws(_to_dev(x), n, slab)
+    torch.cuda.synchronize()
+    assert O.relative_error(y.float().cpu().numpy(), ref) <= TOL
+    tiny = torch.empty((1023 * inn,), dtype=torch.float16, device="cuda:0")
+    with pytest.raises(B.BitStackError) as e:
+        ps.linear_materialised(_to_dev(x[:70]), n, tiny)
+    assert e.value.code == -6
+
+
 def test_materialised_path_argument_errors(B):
     import torch
     L = B.lib()
