@@ -144,6 +144,49 @@ def test_cfg2_device_decomposition_against_full_svd_oracle(B):
     assert err <= 2e-3
 
 
+def test_llama70b_mlp_shape_two_blocks_against_the_subspace_oracle(B):
+    """28672x8192 (the 70B model's MLP shape, 235 M weights): two blocks on the device against the
+    oracle's subspace-iteration decomposition (a full SVD of this size is out of reach for a
+    test).  Block 0's signs exactly, block 1's signs on the residual the device's own block 0
+    leaves, residual norms after each block (unique by Eckart-Young) and sigma_0."""
+    import time
+    import torch
+    out, inn, n = 28672, 8192, 2
+    Wt, s = _weights(5, out, inn)
+    t0 = time.perf_counter()
+    ref = O.iavd(Wt, s, n, 16, method="subspace", iters=24, rng=W.rng_for(5, 1))
+    print(f"70B MLP shape: oracle (subspace, 24 iterations), {n} blocks: {time.perf_counter() - t0:.0f} s on the host", flush=True)
+    Wd = torch.from_numpy(Wt).to("cuda:0")
+    B.decompose(Wd, s, 1, iterations=2)                        # warm-up (first launches, workspace)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    sw, U, V = B.decompose(Wd, s, n)
+    torch.cuda.synchronize()
+    print(f"70B MLP shape: device decomposition: {(time.perf_counter() - t0) * 1e3 / n:.0f} ms per block", flush=True)
+    del Wd
+    sw = sw.cpu().numpy().view(np.uint32)
+    U = U.cpu().numpy()
+    V = V.cpu().numpy()
+    assert np.isfinite(U.astype(np.float64)).all() and np.isfinite(V.astype(np.float64)).all()
+    assert np.array_equal(sw[0], O.pack_signs(ref.S[0]))
+    S = np.stack([O.unpack_signs(sw[i], inn) for i in range(n)])
+    R = np.asarray(Wt, dtype=np.float64) * np.asarray(s, dtype=np.float64)[None, :]
+    R1 = R - O.block_dense(S[0], U[0], V[0])
+    clear = np.abs(R1) > 1e-5 * np.abs(R).max()
+    assert np.array_equal(S[1][clear], O.sign_pm1(R1)[clear])
+    assert (~clear).mean() < 1e-3
+    del R1, clear
+    got = _residual_norms(Wt, s, S, U, V)
+    want = _residual_norms(Wt, s, ref.S, ref.U, ref.V)
+    rel = got[1:] / want[1:] - 1.0
+    print(f"70B MLP shape: ||R_i|| / ||R_0|| on the device {np.array2string(got[1:] / got[0], precision=5)}, "
+          f"device/oracle - 1: {np.array2string(rel, precision=5)}", flush=True)
+    assert np.all(np.abs(rel) < 2e-3) and np.all(np.diff(got) < 0)
+    sig_dev = np.linalg.norm(U[0][:, 0].astype(np.float64)) * np.linalg.norm(V[0][:, 0].astype(np.float64))
+    sig_ref = np.linalg.norm(ref.U[0][:, 0].astype(np.float64)) * np.linalg.norm(ref.V[0][:, 0].astype(np.float64))
+    assert abs(sig_dev / sig_ref - 1.0) < 2e-3
+
+
 def test_blocks_pushed_from_device_arrays_are_the_host_packers_bytes(B):
     """bitstack_push_block_device against bitstack_pack_blocks: the block slots and the row maxima
     of the two images are equal byte for byte, so every kernel sees the same stack."""
