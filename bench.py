@@ -321,6 +321,29 @@ def decoder_token(B, torch, dev, layers=32, n_pack=24):
     gbs = total_bytes / ms / 1e6
     log(f"[bench] decoder token: {len(items)} linears, {total_bytes / 1e9:.2f} GB of blocks, {ms:.3f} ms/token, "
         f"{gbs:.0f} GB/s ({gbs / HBM_PEAK_GBS * 100:.1f}% of 8 TB/s)")
+    # the same token through a plan made once (grouping, work splits and argument blocks are not
+    # recomputed per token); its outputs must be the native loop's, bit for bit
+    ms_plan, plan_steps = None, None
+    try:
+        want = [it[3].clone() for it in items]
+        for it in items:
+            it[3].zero_()
+        plan = B.TokenPlan(jobs)
+        plan_steps = plan.steps
+        plan.launch()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, it[3]) for a, it in zip(want, items)), "plan launch differs from bitstack_linear_many"
+        e0.record()
+        for _ in range(reps):
+            plan.launch()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_plan = e0.elapsed_time(e1) / reps
+        log(f"[bench] decoder token through a plan ({plan_steps} launches): {ms_plan:.3f} ms/token, "
+            f"{total_bytes / ms_plan / 1e6:.0f} GB/s")
+        plan.release()
+    except Exception as ex:
+        log(f"[bench] decoder token plan variant skipped: {type(ex).__name__}: {ex}")
     # the same token as one captured graph (the launches carry no memset nodes); replayed with
     # eager work between replays and compared with the eager outputs
     ms_graph = None
@@ -352,7 +375,8 @@ def decoder_token(B, torch, dev, layers=32, n_pack=24):
     return {"linears": len(items), "block_stream_bytes": total_bytes, "ms_per_token": round(ms, 4),
             "GBps": round(gbs, 1), "pct_of_hbm_peak": round(gbs / HBM_PEAK_GBS * 100, 2),
             "n_loaded": "U{8..24} per matrix, seeded", "launches_per_layer": 4,
-            "ms_per_token_graph": None if ms_graph is None else round(ms_graph, 4)}
+            "ms_per_token_graph": None if ms_graph is None else round(ms_graph, 4),
+            "ms_per_token_plan": None if ms_plan is None else round(ms_plan, 4), "plan_launches": plan_steps}
 
 
 def main():
@@ -361,11 +385,11 @@ def main():
     ap.add_argument("--steps", type=int, default=960)
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--batch-table", action="store_true",
-                    help="(kept for compatibility: the batch kernels of configs 3 and 5 are timed by default)")
+                    help="with --headline-only: also the batch kernels of configs 3 and 5 (they are timed by default otherwise)")
     ap.add_argument("--copies", type=int, default=16, help="separately packed copies to rotate over")
     ap.add_argument("--table", action="store_true", help="(kept for compatibility: the MLP shapes are timed by default)")
     ap.add_argument("--decoder", action="store_true",
-                    help="(kept for compatibility: the decoder token of config 4 is timed by default)")
+                    help="with --headline-only: also the decoder token of config 4 (timed by default otherwise)")
     ap.add_argument("--decompose", action="store_true",
                     help="also time the decomposition on the device (4096x4096 and 14336x4096)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -459,6 +483,14 @@ def main():
         if ceiling:
             extra["config4_decoder_token"]["pct_of_read_ceiling"] = round(
                 extra["config4_decoder_token"]["GBps"] / ceiling["1GiB"] * 100, 1)
+    else:
+        # a profiler run of one table: the headline's launches plus that table's
+        if args.batch_table or args.decoder:
+            del stacks, jobs, items
+        if args.batch_table:
+            extra["config3_5_batch_path"] = batch_table(B, torch, dev, n)
+        if args.decoder:
+            extra["config4_decoder_token"] = decoder_token(B, torch, dev)
     if args.decompose:
         extra["decomposition"] = decompose_table(B, torch, dev)
 
@@ -506,9 +538,9 @@ def main():
 
 
 # HBM bytes per launch of the decode kernel on this workload from rocprofv3 --pmc
-# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); see
-# profiles/decode_4096x4096_n16_pmc.txt (40.38 MB fetched + 1.07 MB written; algorithmic 37.75 MB).
-TRAFFIC_BYTES_PER_LAUNCH = 41443857
+# (FETCH_SIZE + WRITE_SIZE, scaled by a read kernel and a copy of known size); see
+# profiles/decode_4096x4096_n16_pmc.txt (39.15 MB fetched + 0.54 MB written; algorithmic 37.75 MB).
+TRAFFIC_BYTES_PER_LAUNCH = 39693000
 
 if __name__ == "__main__":
     main()
