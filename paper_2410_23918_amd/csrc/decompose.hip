@@ -167,8 +167,24 @@ __global__ __launch_bounds__(256) void k_dc_gram(const float* P, int slices, flo
     for (int e = 0; e < 4; ++e) dst[e] = acc[e];
 }
 
-// the Gram matrix from its parts, in a fixed order, into LDS (256 threads, four entries each)
+// the Gram matrix from its parts, in a fixed order, into LDS: 1024 threads, one entry each, the loads
+// of up to 32 parts in flight together (one trip to memory per 32 parts instead of one per four)
+constexpr int kSmallThreads = kL * kL;
 __device__ __forceinline__ void gram_sum(const double* Gpart, int parts, double (*Gs)[kL + 1]) {
+    const int e = threadIdx.x;
+    double acc = 0.0;
+    for (int p0 = 0; p0 < parts; p0 += 32) {
+        double v[32];
+#pragma unroll
+        for (int u = 0; u < 32; ++u) v[u] = p0 + u < parts ? Gpart[size_t(p0 + u) * (kL * kL) + e] : 0.0;
+#pragma unroll
+        for (int u = 0; u < 32; ++u) acc += v[u];   // the order of the additions is fixed
+    }
+    Gs[e / kL][e % kL] = acc;
+}
+
+// the Gram matrix from its parts, in a fixed order, into LDS (256 threads, four entries each)
+__device__ __forceinline__ void gram_sum4(const double* Gpart, int parts, double (*Gs)[kL + 1]) {
     const int e0 = threadIdx.x * 4;
     double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
     typedef double d2 __attribute__((ext_vector_type(2)));
@@ -201,7 +217,7 @@ __global__ __launch_bounds__(256) void k_dc_chol_inv(const double* Gpart, int pa
     __shared__ double Gs[kL][kL + 1];
     __shared__ double Lr[kL][kL + 1];
     const int t = threadIdx.x;
-    gram_sum(Gpart, parts, Gs);
+    gram_sum4(Gpart, parts, Gs);
     __syncthreads();
     if (t >= 64) return;   // the factorisation is one wavefront's work; its barriers then cost little
     double a[kL];
@@ -291,21 +307,21 @@ __global__ __launch_bounds__(256) void k_dc_apply(const float* Y, const float* T
 // H diag(sigma^2) H^T gives the leading triplets of |R|: left vectors Q H, right vectors
 // Z H diag(1/sigma).  Tu = H_k diag(sqrt(sigma)), Tv = H_k diag(1/sqrt(sigma)) (Eq. 2's split):
 // U = Q Tu, V = Z Tv.  Jacobi rotations in fp64 in the round-robin ordering: 31 rounds of 16
-// disjoint pairs per sweep, the 16 rotations of a round applied together (32 of the 256 threads;
-// all of them add up the parts of G first).
-__global__ __launch_bounds__(256) void k_dc_ritz(const double* Gpart, int parts, float* Tu, float* Tv, int k) {
+// disjoint pairs per sweep, the 16 rotations of a round applied together by 512 threads, one per
+// (line, pair); all 1024 add up the parts of G first.
+__global__ __launch_bounds__(kSmallThreads) void k_dc_ritz(const double* Gpart, int parts, float* Tu, float* Tv, int k) {
     __shared__ double A[kL][kL + 1];
     __shared__ double H[kL][kL + 1];
     __shared__ double cs[kL / 2][2];
     __shared__ int pq[kL / 2][2];
     __shared__ int order[kL];
+    __shared__ double offd[kL];
     const int t = threadIdx.x;
     gram_sum(Gpart, parts, A);
-    if (t < kL)
-        for (int c = 0; c < kL; ++c) H[t][c] = (t == c) ? 1.0 : 0.0;
+    H[t / kL][t % kL] = (t / kL == t % kL) ? 1.0 : 0.0;
     __syncthreads();
-    if (t >= 64) return;   // the rotations are one wavefront's work
-    __shared__ double offd[kL];
+    // thread (line r, pair e) of the first 512 applies rotation e of a round to line r
+    const int r = t >> 4, e = t & (kL / 2 - 1);
     for (int sweep = 0; sweep < 10; ++sweep) {
         // converged?  (off-diagonal mass against the trace; falls quadratically once small)
         if (t < kL) {
@@ -345,46 +361,21 @@ __global__ __launch_bounds__(256) void k_dc_ritz(const double* Gpart, int parts,
                 cs[t][1] = s;
             }
             __syncthreads();
-            // the 16 pairs are disjoint: all reads of a phase first (in flight together), then the writes
-            int pp[kL / 2], qq[kL / 2];
-            double cc[kL / 2], ss[kL / 2];
-#pragma unroll
-            for (int e = 0; e < kL / 2; ++e) {
-                pp[e] = pq[e][0];
-                qq[e] = pq[e][1];
-                cc[e] = cs[e][0];
-                ss[e] = cs[e][1];
-            }
-            if (t < kL) {   // columns p, q of A and H for every pair: row t
-                double ap[kL / 2], aq[kL / 2], hp[kL / 2], hq[kL / 2];
-#pragma unroll
-                for (int e = 0; e < kL / 2; ++e) {
-                    ap[e] = A[t][pp[e]];
-                    aq[e] = A[t][qq[e]];
-                    hp[e] = H[t][pp[e]];
-                    hq[e] = H[t][qq[e]];
-                }
-#pragma unroll
-                for (int e = 0; e < kL / 2; ++e) {
-                    A[t][pp[e]] = cc[e] * ap[e] - ss[e] * aq[e];
-                    A[t][qq[e]] = ss[e] * ap[e] + cc[e] * aq[e];
-                    H[t][pp[e]] = cc[e] * hp[e] - ss[e] * hq[e];
-                    H[t][qq[e]] = ss[e] * hp[e] + cc[e] * hq[e];
-                }
+            // the 16 pairs of a round are disjoint: 512 threads, one (line, pair) each
+            const int p = pq[e][0], q = pq[e][1];
+            const double c = cs[e][0], sn = cs[e][1];
+            if (t < kL * kL / 2) {   // columns p, q of A and H: row r
+                const double ap = A[r][p], aq = A[r][q], hp = H[r][p], hq = H[r][q];
+                A[r][p] = c * ap - sn * aq;
+                A[r][q] = sn * ap + c * aq;
+                H[r][p] = c * hp - sn * hq;
+                H[r][q] = sn * hp + c * hq;
             }
             __syncthreads();
-            if (t < kL) {   // rows p, q of A for every pair: column t
-                double ap[kL / 2], aq[kL / 2];
-#pragma unroll
-                for (int e = 0; e < kL / 2; ++e) {
-                    ap[e] = A[pp[e]][t];
-                    aq[e] = A[qq[e]][t];
-                }
-#pragma unroll
-                for (int e = 0; e < kL / 2; ++e) {
-                    A[pp[e]][t] = cc[e] * ap[e] - ss[e] * aq[e];
-                    A[qq[e]][t] = ss[e] * ap[e] + cc[e] * aq[e];
-                }
+            if (t < kL * kL / 2) {   // rows p, q of A: column r
+                const double ap = A[p][r], aq = A[q][r];
+                A[p][r] = c * ap - sn * aq;
+                A[q][r] = sn * ap + c * aq;
             }
             __syncthreads();
         }
@@ -530,7 +521,7 @@ hipError_t launch_decompose(const float* W, const float* s, int out, int in, int
         }
         mul(true, Q);
         hipLaunchKernelGGL(k_dc_gram, dim3((in + kGramRows - 1) / kGramRows), dim3(256), 0, st, P, slices, Z, in, G);
-        hipLaunchKernelGGL(k_dc_ritz, dim3(1), dim3(256), 0, st, G, (in + kGramRows - 1) / kGramRows, Tu, Tv, kRank);
+        hipLaunchKernelGGL(k_dc_ritz, dim3(1), dim3(kSmallThreads), 0, st, G, (in + kGramRows - 1) / kGramRows, Tu, Tv, kRank);
         hipLaunchKernelGGL((k_dc_apply<kRank, true>), dim3((out + 255) / 256), dim3(256), 0, st, Q, Tu, Ui, out);
         hipLaunchKernelGGL((k_dc_apply<kRank, true>), dim3((in + 255) / 256), dim3(256), 0, st, Z, Tv, Vi, in);
         hipLaunchKernelGGL(k_dc_update, dim3((in + 63) / 64, (out + 31) / 32), dim3(256), 0, st, R, Ui, Vi, out, in);
