@@ -652,6 +652,29 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
 #ifdef BITSTACK_TRACE
     const bool finishing = *flag != 0;
 #endif
+    // Few partial rows per slab and one row per thread (R = 2): every thread adds up its row over all
+    // slots, their loads in flight together, in slot order (fixed: the result does not depend on
+    // which workgroup arrived last); no LDS, no barrier.  Measured 0.45 us faster than the general
+    // path below at 32 slots, and slower beyond (a second round of loads) and with two rows per thread.
+    if (R == 2 && *flag && p.n_ks * p.n_bg <= 32) {
+        const int nslots = p.n_ks * p.n_bg;
+        const int row = row0 + tid;
+        const bool live = row < p.out;
+        const unsigned span = unsigned(size_t(nslots) * p.out * 4);
+        __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(p.part, 0, span, 0x00020000);
+        constexpr int kAgentScope = 16;   // sc1
+        int v[32];
+#pragma unroll
+        for (int k = 0; k < 32; ++k) {
+            const unsigned off = (live && k < nslots) ? unsigned((size_t(k) * p.out + row) * 4) : span;
+            v[k] = __builtin_amdgcn_raw_buffer_load_b32(prs, off, 0, kAgentScope);
+        }
+        float tot = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 32; ++k) tot += __int_as_float(v[k]);   // slots past the end read as zero
+        if (live) store_y(p, size_t(row), tot);
+        if (tid == 0) __hip_atomic_store(&p.ctr[rs_i * kCounterStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else
     if (*flag) {
         // One pass with every load in flight at once: thread = (4 consecutive rows, every NSG-th
         // slot), 128-bit loads; the NSG partial sums of a row quad meet in LDS.  Fixed summation
