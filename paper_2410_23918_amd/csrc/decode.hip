@@ -217,7 +217,6 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
         return raw;
     };
     Raw raw = load_raw(0);       // interval 0, quantised in the prologue
-    Raw raw_cur = load_raw(1);   // interval 1 (used by the wavefronts that quantise at the start of an interval)
     // The two wavefronts of a SIMD share its issue port and the older one is served first: it
     // finishes an interval's matrix-core work well before the younger one.  So the younger one
     // (wavefronts 4..7) quantises its share of the next panel at the start of an interval, while
@@ -481,6 +480,10 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
         }
     };
 
+    // interval 1's V values (used first by the wavefronts that quantise at the start of an interval):
+    // requested only now, so that the requests of the prologue that matter sooner (x, maxima, the
+    // first panel's V, the first sign units) do not share the compute unit's memory queue with them
+    Raw raw_cur = load_raw(1);
     quantise(0, raw);
     BS_TR(4);
 #pragma unroll
