@@ -207,7 +207,8 @@ def batch_table(B, torch, dev, n):
         return e0.elapsed_time(e1) * 1e3 / reps
 
     rows = []
-    names = {B.KERNEL_DECODE: "decode kernel, up to four tokens per launch", B.KERNEL_PANEL: None}
+    names = {B.KERNEL_DECODE: "decode kernel, up to four tokens per launch", B.KERNEL_PANEL: None,
+             B.KERNEL_MATERIALISE: "restore + k_gemm in row slabs through the image's own activation scratch"}
     for cfg, (o, i), batches in ((3, (14336, 4096), (4, 16, 64, 512, 2048)), (3, (4096, 14336), (4, 16)),
                                  (5, (28672, 8192), (128, 2048))):
         st = build_stack(o, i, n, cfg)
@@ -226,6 +227,14 @@ def batch_table(B, torch, dev, n):
             log(f"[bench] batch path {o}x{i} n={n} tokens={b} ({kern}): {us:.1f} us, {tf:.1f} useful TFLOP/s")
             rows.append({"shape": f"{o}x{i}", "tokens": b, "kernel": kern, "us": round(us, 1),
                          "useful_TFLOPs": round(tf, 2)})
+            if B.choose_kernel(o, i, n, max(batches), b, n) == B.KERNEL_MATERIALISE:
+                # the kernel that rebuilds weight tiles on chip, for comparison
+                ut = timed(lambda: ps.linear_batched(x, n, y=y, kernel=B.KERNEL_PANEL), 3)
+                tft = 2.0 * o * i * b / ut / 1e6
+                log(f"[bench] batch path {o}x{i} n={n} tokens={b} (k_xpack + k_tile, forced): {ut:.1f} us, "
+                    f"{tft:.1f} useful TFLOP/s")
+                rows.append({"shape": f"{o}x{i}", "tokens": b, "kernel": "k_xpack + k_tile (forced)", "us": round(ut, 1),
+                             "useful_TFLOPs": round(tft, 2)})
             if b > 64:
                 y2 = torch.empty_like(y)
                 um = timed(lambda: ps.linear_materialised(x, n, wd, y=y2), 3)

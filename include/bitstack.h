@@ -71,8 +71,11 @@ enum {
     BITSTACK_KERNEL_DECODE    = 2, /* matrix-core sign-stream kernel, up to 4 tokens per launch  */
     BITSTACK_KERNEL_PANEL     = 3, /* batch kernels: weight rebuilt on chip (Eq. 8) and multiplied
                                       with the activations on the matrix cores, any batch        */
-    BITSTACK_KERNEL_MATERIALISE = 4 /* restore the weight to a dense scratch, then a dense product;
-                                       needs a scratch buffer: bitstack_linear_batched_ws only   */
+    BITSTACK_KERNEL_MATERIALISE = 4 /* restore the weight to a dense scratch, then a dense product:
+                                       the scratch lent to bitstack_linear_batched_ws, else the
+                                       activation scratch inside an image packed with
+                                       max_batch > 64 (BITSTACK_E_BUFSIZE if that holds fewer
+                                       than 1024 rows of the dense weight)                       */
 };
 
 /* Bytes of one residual block: (out*in + 16*k*(out+in)) / 8, Eq. (9) of the
@@ -273,7 +276,11 @@ void bitstack_plan_release(bitstack_plan_t* plan);
 
 /* Same for a batch of tokens.  x: device fp16 [batch][in] row-major;
  * y: device [batch][out] row-major of y_dtype (BITSTACK_Y_F16 / BITSTACK_Y_F32);
- * 1 <= batch <= max_batch given at pack time. */
+ * 1 <= batch <= max_batch given at pack time.  The library picks the kernel from the shape,
+ * the batch and the number of loaded blocks; for prefill-sized batches that can be the
+ * materialising path below in row slabs through the image's own activation scratch
+ * (max_batch x in x 2 bytes, there in every image packed with max_batch > 64), when that
+ * holds at least 1024 rows of the dense weight. */
 int bitstack_linear_batched(const void* x, int batch, const bitstack_weight_t* blocks,
                             int n_loaded, void* y, int y_dtype, bitstack_stream_t stream);
 
@@ -311,7 +318,9 @@ int bitstack_restore_max_blocks(void);
  * aligned, may be NULL): when it holds at least 1024 rows of the dense weight (1024 x in x 2
  * bytes; the whole matrix, bitstack_dense_bytes(out, in), avoids slabs) and the materialising
  * path is estimated to be faster for this batch and stack height, that path is taken and
- * overwrites the buffer; otherwise the buffer is left alone.  Same results contract and errors as bitstack_linear_batched.
+ * overwrites the buffer; otherwise the buffer is left alone.  A buffer smaller than the image's
+ * own activation scratch is left alone too (the image's is used where the path is taken).
+ * Same results contract and errors as bitstack_linear_batched.
  * bitstack_choose_kernel (host only, no device work) returns the BITSTACK_KERNEL_* value that
  * call would pick for a stack of this shape (BITSTACK_KERNEL_AUTO for n_loaded = 0, where y is
  * only cleared), or a negative error code for an unsupported shape / out-of-range arguments. */

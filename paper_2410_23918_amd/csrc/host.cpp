@@ -313,8 +313,16 @@ static int slab_rows(const Geometry& g, size_t workspace_bytes) {
     return rows >= 1024 ? rows : 0;
 }
 
+// The scratch the materialising path works in: the caller's, or -- when none is lent or the image's
+// is larger -- the image's own activation scratch, which only the weight-tile kernel uses (the
+// dense product reads x in place).  Images packed for at most 64 tokens have none.
+static size_t scratch_bytes(const Geometry& g, size_t workspace_bytes) {
+    return workspace_bytes >= g.xpack_bytes ? workspace_bytes : g.xpack_bytes;
+}
+
 static int choose_kernel(const Geometry& g, int batch, int n_loaded, size_t workspace_bytes) {
     if (batch == 1) return BITSTACK_KERNEL_DECODE;
+    workspace_bytes = scratch_bytes(g, workspace_bytes);
     const double t_decode = decode_tokens_time_us(g, batch, n_loaded);   // up to four tokens per launch
     double t_panel;
     if (batch <= kSmallBatch) {
@@ -382,8 +390,12 @@ static int linear_impl(const void* x, int batch, const bitstack_weight_t* w, int
                 e = launch_panel(a, st);
                 break;
             case BITSTACK_KERNEL_MATERIALISE:
-                return bitstack_linear_materialised(x, batch, w, n_loaded, workspace, workspace ? workspace_bytes : 0, y,
-                                                    y_dtype, stream);
+                if (!workspace || workspace_bytes < g.xpack_bytes) {   // the image's own scratch (see scratch_bytes)
+                    if (!g.xpack_bytes) return BITSTACK_E_BUFSIZE;
+                    workspace = w->dev + g.off_xpack;
+                    workspace_bytes = g.xpack_bytes;
+                }
+                return bitstack_linear_materialised(x, batch, w, n_loaded, workspace, workspace_bytes, y, y_dtype, stream);
             default:
                 return BITSTACK_E_ARG;
         }
@@ -394,7 +406,6 @@ static int linear_impl(const void* x, int batch, const bitstack_weight_t* w, int
 
 int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* w, int n_loaded, void* y,
                            int y_dtype, int kernel, bitstack_stream_t stream) {
-    if (kernel == BITSTACK_KERNEL_MATERIALISE) return BITSTACK_E_ARG;   // needs a scratch buffer: bitstack_linear_batched_ws
     return linear_impl(x, batch, w, n_loaded, y, y_dtype, kernel, nullptr, 0, stream);
 }
 

@@ -138,18 +138,24 @@ def test_staged_block_equals_its_slot_in_the_whole_image():
 
 def test_kernel_choice_is_host_logic():
     """bitstack_choose_kernel: one token always takes the decode kernel; the materialising path is
-    chosen only with a scratch buffer of at least 1024 rows of the dense weight and a stack the
-    restore kernel can hold, and only for prefill-sized batches."""
+    chosen only with a scratch of at least 1024 rows of the dense weight -- the caller's, or the
+    activation scratch inside an image packed for that many tokens -- and a stack the restore
+    kernel can hold, and only for prefill-sized batches."""
     import paper_2410_23918_amd as B
     big = 1 << 40
     assert B.choose_kernel(4096, 4096, 16, 1, 1, 16) == B.KERNEL_DECODE
     assert B.choose_kernel(4096, 4096, 16, 2048, 1, 16, big) == B.KERNEL_DECODE
     assert B.choose_kernel(28672, 8192, 16, 2048, 2048, 16, big) == B.KERNEL_MATERIALISE
-    assert B.choose_kernel(28672, 8192, 16, 2048, 2048, 16, 0) == B.KERNEL_PANEL
+    # no scratch lent: an image packed for 2048 tokens carries 2048 x in fp16 of activation scratch, which
+    # holds 2048 rows of the dense weight at a time; one packed for 1000 tokens has too little
+    assert B.choose_kernel(28672, 8192, 16, 2048, 2048, 16, 0) == B.KERNEL_MATERIALISE
+    assert B.choose_kernel(28672, 8192, 16, 2048, 512, 16, 0) == B.KERNEL_PANEL
+    assert B.choose_kernel(28672, 8192, 16, 1000, 1000, 16, 0) == B.KERNEL_PANEL
     # a scratch for fewer rows than the weight has serves slab by slab, down to 1024 rows; below that it is ignored
     assert B.choose_kernel(28672, 8192, 16, 2048, 2048, 16, B.dense_bytes(28672, 8192) - 1) == B.KERNEL_MATERIALISE
     assert B.choose_kernel(28672, 8192, 16, 2048, 2048, 16, 64 << 20) == B.KERNEL_MATERIALISE
-    assert B.choose_kernel(28672, 8192, 16, 2048, 2048, 16, 1024 * 8192 * 2 - 1) == B.KERNEL_PANEL
+    assert B.choose_kernel(28672, 8192, 16, 1000, 1000, 16, 64 << 20) == B.KERNEL_MATERIALISE
+    assert B.choose_kernel(28672, 8192, 16, 1000, 1000, 16, 1024 * 8192 * 2 - 1) == B.KERNEL_PANEL
     assert B.choose_kernel(28672, 8192, 16, 2048, 2048, 16, B.dense_bytes(28672, 8192)) == B.KERNEL_MATERIALISE
     assert B.choose_kernel(28672, 8192, 16, 2048, 128, 16, big) == B.KERNEL_PANEL
     assert B.choose_kernel(14336, 4096, 32, 2048, 2048, B.restore_max_blocks() + 1, big) == B.KERNEL_PANEL

@@ -703,8 +703,40 @@ def test_library_choice_with_an_optional_scratch_buffer(B):
     L = B.lib()
     assert L.bitstack_linear_batched_ws(C.c_void_p(y.data_ptr()), 1, ps.handle, n, C.c_void_p(y.data_ptr()), 0,
                                         C.c_void_p(ws.data_ptr() + 16), ws.numel() * 2, None) == -4
-    assert L.bitstack_linear_select(C.c_void_p(y.data_ptr()), 1, ps.handle, n, C.c_void_p(y.data_ptr()), 0,
-                                    B.KERNEL_MATERIALISE, None) == -8
+
+
+def test_materialised_path_through_the_images_own_scratch(B):
+    """No scratch lent: an image packed for many tokens carries max_batch x in fp16 of activation
+    scratch (the weight-tile kernel's), which the materialising path uses for slabs of the dense
+    weight.  Forced through the kernel selector: same bits as through a caller's scratch for the
+    whole matrix; the weight-tile kernel, which writes activations there, still works afterwards;
+    an image packed for at most 64 tokens has no such scratch and the selector is refused."""
+    import torch
+    out, inn, n = 2336, 1024, 3       # 1120 tokens of scratch = 1024 rows at a time: slabs of 1024, 1024, 288
+    st = synth_stack(3, out, inn, n)
+    ps = _pack(B, st, max_batch=1100)
+    x = acts(3, 1100, inn)
+    ref = O.forward_dense(st, x, n)
+    full = torch.empty((out, inn), dtype=torch.float16, device="cuda:0")
+    for b in (70, 1100):
+        xd = _to_dev(x[:b])
+        for dt in (torch.float16, torch.float32):
+            y_full = ps.linear_materialised(xd, n, full, out_dtype=dt)
+            y_img = ps.linear_batched(xd, n, out_dtype=dt, kernel=B.KERNEL_MATERIALISE)
+            y_tile = ps.linear_batched(xd, n, out_dtype=dt, kernel=B.KERNEL_PANEL)
+            torch.cuda.synchronize()
+            assert torch.equal(y_full, y_img), (b, dt)
+            for name, y in (("materialised through the image's scratch", y_img), ("batch kernel after it", y_tile)):
+                err = _report(f"{out}x{inn} B={b} {dt}, {name}", y.float().cpu().numpy(), ref[:b])
+                assert err <= TOL
+    # a caller's scratch smaller than the image's is left alone
+    small = torch.full((1024 * inn,), 7.0, dtype=torch.float16, device="cuda:0")
+    assert B.choose_kernel(out, inn, n, 1100, 1100, n, small.numel() * 2) == B.choose_kernel(out, inn, n, 1100, 1100, n, 0)
+    few = _pack(B, st, max_batch=64)
+    y = torch.empty((8, out), dtype=torch.float16, device="cuda:0")
+    L = B.lib()
+    assert L.bitstack_linear_select(C.c_void_p(_to_dev(x[:8]).data_ptr()), 8, few.handle, n, C.c_void_p(y.data_ptr()), 0,
+                                    B.KERNEL_MATERIALISE, None) == -6
 
 
 def test_materialised_path_in_row_slabs_through_a_small_scratch(B):
