@@ -231,7 +231,14 @@ int bitstack_manager_n_loaded(const bitstack_manager_t* m, int stack);
  *   y = ( sum_{i < n_loaded} S_i (.) (U_i V_i^T) ) diag(1/s) x           (Eq. 4 + Eq. 8)
  *   x: device fp16 [in], 16-byte aligned.   y: device fp16 [out], 16-byte aligned.
  *   n_loaded in [0, resident blocks]: the prefix of the stack to use; 0 gives y = 0.
- * Asynchronous: work is enqueued on stream and the call returns. */
+ * Asynchronous: work is enqueued on stream and the call returns.
+ * Accuracy: sums are exact integers or fp32 and y is rounded once; the one lossy step is the panel
+ *   diag(x/s) V_i, held as 16-bit fixed point against its largest entry per block and range of up
+ *   to 8192 columns, with groups of 32 columns that are at least 4x quieter kept 4x or 8x finer.
+ *   Measured against an fp64 evaluation, max |y - y_ref| / max |y_ref| is 3e-4 ... 5e-4 for
+ *   Gaussian activations and stays below 1e-3 with 1 to 32 channels 30x to 1000x above the
+ *   rest and for heavy-tailed (Student-t, 3 degrees of freedom) activations; the bound this path
+ *   is held to is 2e-3.  x/s is formed in fp32 and must stay finite in it; a zero x gives y = 0. */
 int bitstack_linear(const void* x, const bitstack_weight_t* blocks, int n_loaded,
                     void* y, bitstack_stream_t stream);
 

@@ -344,12 +344,13 @@ def test_degenerate_activations(B):
 
 
 def _outlier_activations(inn):
-    """x ~ N(0,1) with 1, 4 and 32 channels at 30x and 100x, and a Student-t(3) draw: a few channels
-    far above the rest is the situation activation-aware scaling (Eq. 3-4) exists for."""
+    """x ~ N(0,1) with 1, 4 and 32 channels at 30x and 100x, 1 and 4 at 1000x, and a Student-t(3)
+    draw: a few channels far above the rest is the situation activation-aware scaling (Eq. 3-4)
+    exists for."""
     base = acts(2, 1, inn, tag=9).astype(np.float32)
     cases = []
-    for fac in (30.0, 100.0):
-        for cnt in (1, 4, 32):
+    for fac, counts in ((30.0, (1, 4, 32)), (100.0, (1, 4, 32)), (1000.0, (1, 4))):
+        for cnt in counts:
             x = base.copy()
             x[0, W.rng_for(2, 77, cnt, int(fac)).choice(inn, cnt, replace=False)] *= fac
             cases.append((f"{cnt} channel(s) x{fac:g}", x.astype(np.float16)))
