@@ -253,11 +253,12 @@ def batch_table(B, torch, dev, n):
                     y3 = torch.empty_like(y)
                     usl = timed(lambda: ps.linear_materialised(x, n, slab, y=y3), 3)
                     tfs = 2.0 * o * i * b / usl / 1e6
-                    same = bool(torch.equal(y3, y2))
+                    # (the product's output tile is chosen per slab, so the last bits may differ)
+                    dslab = (y3.float() - y2.float()).abs().max().item() / y2.float().abs().max().item()
                     log(f"[bench] materialising path in row slabs, 128 MiB scratch, {o}x{i} n={n} tokens={b}: "
-                        f"{usl:.1f} us, {tfs:.1f} useful TFLOP/s; same bits as with the full scratch: {same}")
+                        f"{usl:.1f} us, {tfs:.1f} useful TFLOP/s; max |difference| to the full scratch / max |y| = {dslab:.1e}")
                     rows.append({"shape": f"{o}x{i}", "tokens": b, "kernel": "restore + k_gemm in row slabs, 128 MiB scratch",
-                                 "us": round(usl, 1), "useful_TFLOPs": round(tfs, 2), "same_bits_as_full_scratch": same})
+                                 "us": round(usl, 1), "useful_TFLOPs": round(tfs, 2), "max_diff_to_full_scratch": dslab})
         del ps, wd
     return rows
 

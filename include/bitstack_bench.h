@@ -22,7 +22,9 @@ enum {
                                              walks every BGROUPS-th block of the loaded prefix (single calls) */
     BITSTACK_OPT_DECODE_TILES = 4,        /* 32-row tiles per wavefront: 2 or 4 (512 / 1024 rows per workgroup) */
     BITSTACK_OPT_DECODE_KS_CHUNKS = 5,    /* 256-column chunks per workgroup: 1..32 */
-    BITSTACK_OPT_DECODE_EARLY = 6         /* value - 1 = chunks of the first sign window requested at entry: 0, 2, 4 */
+    BITSTACK_OPT_DECODE_EARLY = 6,        /* value - 1 = chunks of the first sign window requested at entry: 0, 2, 4 */
+    BITSTACK_OPT_DENSE_TILE = 7           /* output tile of the dense product: 1 = 256 rows x 256 tokens, 2 = 128 x 256,
+                                             3 = 128 x 128 */
 };
 int bitstack_set_option(int option, int value);
 

@@ -11,7 +11,7 @@ from .binding import (  # noqa: F401
     order_check,
     budget_position,
     KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL, KERNEL_MATERIALISE,
-    OPT_DECODE_BGROUPS, OPT_DECODE_TILES, OPT_DECODE_KS_CHUNKS, OPT_DECODE_EARLY,
+    OPT_DECODE_BGROUPS, OPT_DECODE_TILES, OPT_DECODE_KS_CHUNKS, OPT_DECODE_EARLY, OPT_DENSE_TILE,
     block_bytes,
     block_staging_bytes,
     dense_bytes,

@@ -12,7 +12,7 @@ _lib = None
 
 KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_DECODE, KERNEL_PANEL, KERNEL_MATERIALISE = 0, 1, 2, 3, 4
 Y_F16, Y_F32 = 0, 1
-OPT_DECODE_BGROUPS, OPT_DECODE_TILES, OPT_DECODE_KS_CHUNKS, OPT_DECODE_EARLY = 3, 4, 5, 6
+OPT_DECODE_BGROUPS, OPT_DECODE_TILES, OPT_DECODE_KS_CHUNKS, OPT_DECODE_EARLY, OPT_DENSE_TILE = 3, 4, 5, 6, 7
 
 
 class BitStackError(RuntimeError):

@@ -18,8 +18,9 @@
 // 128-bit reads) and issues eight v_mfma_f32_32x32x16_f16; the other wavefront of the SIMD covers
 // the read latency.  One LDS-only barrier per chunk.  The fp16 output tile is turned in LDS and
 // leaves in 16-byte pieces.  Workgroup ids map to tiles so that all token tiles of a row tile run
-// on one XCD (one L2 pulls that part of the weight).  A second instantiation with 128-row tiles
-// fills the chip for shapes with few row tiles (chosen per launch on the host).
+// on one XCD (one L2 pulls that part of the weight).  Two more instantiations, with tiles of 128
+// rows x 256 tokens and of 128 x 128, fill the chip for shapes with few tiles (row slabs, small
+// batches; chosen per launch on the host).
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -49,28 +50,39 @@ __global__ __launch_bounds__(256) void k_dense_zero(uint4* w, size_t n16) {
 // RJ: 32-row fragments per wavefront.  4: the 256-row tile described above.  2: a 128-row tile
 // (wavefront tile 64 rows x 64 tokens, four matrix instructions per step), for shapes whose
 // 256-row tiles would leave half of the compute units without a workgroup.
-template <int RJ>
+// KSPLIT (with RJ = 2): a tile of 128 rows x 128 tokens for products too small to fill the chip
+// with the wider tiles (a slab of 2048 rows x 2048 tokens is 256 of these).  The wavefront tile
+// stays 64 x 64 (one LDS fragment per matrix instruction, as in the 128-row variant): wavefronts
+// 0-3 take the first 32 columns of every chunk, wavefronts 4-7 the other 32, and the two halves
+// are added through LDS after the loop.
+template <int RJ, bool KSPLIT>
 __global__ __launch_bounds__(512) void k_gemm(KParams p) {
-    constexpr int ROWS = 64 * RJ;
+    static_assert(!KSPLIT || RJ == 2, "the 128 x 128 tile is built from 64 x 64 wavefront tiles");
+    constexpr int ROWS = KSPLIT ? 128 : 64 * RJ;
+    constexpr int TOKS = KSPLIT ? 128 : kGemmTokens;
+    constexpr int STEPS = KSPLIT ? 2 : 4;   // 16-column steps of a chunk per wavefront
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     _Float16* const wl = reinterpret_cast<_Float16*>(smem);   // [buffer][256 rows][kGemmLd]
     _Float16* const xl = wl + 2 * kGemmTile;                   // [buffer][256 tokens][kGemmLd]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hl = lane >> 5, ln = lane & 31;
-    const int tg = wave & 3, rg = wave >> 2;   // my 64 tokens and 32 RJ rows inside the workgroup's tile
+    // my 64 tokens and 32 RJ rows inside the workgroup's tile (and, KSPLIT, my half of every chunk)
+    const int tg = KSPLIT ? (wave & 1) : (wave & 3), rg = KSPLIT ? ((wave >> 1) & 1) : (wave >> 2);
+    const int kh = KSPLIT ? (wave >> 2) : 0;
 
     // Workgroup ids are dealt round-robin to the 8 XCDs: all token tiles of a row tile go to one
     // XCD, so that a weight tile is pulled into one L2 only.
-    const int ntt = (p.batch + kGemmTokens - 1) / kGemmTokens, nrt = (p.out + ROWS - 1) / ROWS;
+    const int ntt = (p.batch + TOKS - 1) / TOKS, nrt = (p.out + ROWS - 1) / ROWS;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int rt = xcd + 8 * (slot / ntt), tt = slot % ntt;
     if (rt >= nrt) return;
-    const int row0 = rt * ROWS, tok0 = tt * kGemmTokens;
+    const int row0 = rt * ROWS, tok0 = tt * TOKS;
     const int nkc = p.in / kGemmKc;   // a multiple of 4
 
     // both tiles of a chunk: thread (row tid/8 + 64 i, 16-byte piece tid%8), i = 0..3 (weight
-    // rows: i < RJ); rows and tokens past the end repeat the last one (computed, never stored)
+    // rows: i < RJ; tokens: i < 2 in the 128-token tile); rows and tokens past the end repeat the
+    // last one (computed, never stored)
     const unsigned char* const wbase = reinterpret_cast<const unsigned char*>(p.wdense);
     const unsigned char* const xbase = reinterpret_cast<const unsigned char*>(p.x);
     // (scalar variables and macros on purpose: arrays or structs of 128 bytes of load results
@@ -100,8 +112,10 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
         }                                                                                  \
         x##S##0 = ld16(xbase, xo0 + c);                                                    \
         x##S##1 = ld16(xbase, xo1 + c);                                                    \
-        x##S##2 = ld16(xbase, xo2 + c);                                                    \
-        x##S##3 = ld16(xbase, xo3 + c);                                                    \
+        if constexpr (!KSPLIT) {                                                           \
+            x##S##2 = ld16(xbase, xo2 + c);                                                \
+            x##S##3 = ld16(xbase, xo3 + c);                                                \
+        }                                                                                  \
     }
 #define BS_GEMM_WRITE(S, BUF)                                                              \
     {                                                                                      \
@@ -113,12 +127,14 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
         }                                                                                  \
         st16(xl, BUF, 0, x##S##0);                                                         \
         st16(xl, BUF, 1, x##S##1);                                                         \
-        st16(xl, BUF, 2, x##S##2);                                                         \
-        st16(xl, BUF, 3, x##S##3);                                                         \
+        if constexpr (!KSPLIT) {                                                           \
+            st16(xl, BUF, 2, x##S##2);                                                     \
+            st16(xl, BUF, 3, x##S##3);                                                     \
+        }                                                                                  \
     }
     // fragments of step s (16 columns) of the chunk in buffer buf: weight rows j*32.., tokens t*32..
-    const _Float16* const wfr = wl + (rg * (32 * RJ) + ln) * kGemmLd + 8 * hl;
-    const _Float16* const xfr = xl + (tg * 64 + ln) * kGemmLd + 8 * hl;
+    const _Float16* const wfr = wl + (rg * (32 * RJ) + ln) * kGemmLd + 8 * hl + kh * 32;
+    const _Float16* const xfr = xl + (tg * 64 + ln) * kGemmLd + 8 * hl + kh * 32;
     auto wfrag = [&](int buf, int s, int j) -> v8h {
         return *reinterpret_cast<const v8h*>(wfr + buf * kGemmTile + j * 32 * kGemmLd + s * 16);
     };
@@ -134,7 +150,7 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][t][v] = 0.0f;
 
-    uint4 wA0, wA1, wA2 = {}, wA3 = {}, xA0, xA1, xA2, xA3, wB0, wB1, wB2 = {}, wB3 = {}, xB0, xB1, xB2, xB3;
+    uint4 wA0, wA1, wA2 = {}, wA3 = {}, xA0, xA1, xA2 = {}, xA3 = {}, wB0, wB1, wB2 = {}, wB3 = {}, xB0, xB1, xB2 = {}, xB3 = {};
     BS_GEMM_LOAD(A, 0)
     BS_GEMM_LOAD(B, 1)
     BS_GEMM_WRITE(A, 0)
@@ -148,7 +164,7 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
     // the second wavefront of the SIMD covers that latency.
 #define BS_GEMM_CHUNK(KC, BUF, S)                                                          \
     {                                                                                      \
-        _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                    \
+        _Pragma("unroll") for (int s = 0; s < STEPS; ++s) {                                \
             if (s == 1) {                                                                  \
                 BS_GEMM_WRITE(S, (BUF) ^ 1)                                                \
                 BS_GEMM_LOAD(S, (KC) + 3)                                                  \
@@ -173,8 +189,33 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
 #undef BS_GEMM_LOAD
 #undef BS_GEMM_WRITE
 
+    if constexpr (KSPLIT) {
+        // the two column halves meet: wavefronts 4-7 park their tiles in LDS (the operand buffers are
+        // free: the loop's last barrier has passed), wavefronts 0-3 add them to theirs
+        float* const red = reinterpret_cast<float*>(smem) + (wave & 3) * (64 * 64) + lane;   // [4][64 registers][64 lanes]
+        if (kh == 1) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) red[((j * 2 + t) * 16 + v) * 64] = acc[j][t][v];
+        }
+        lds_barrier();
+        if (kh == 0) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[j][t][v] += red[((j * 2 + t) * 16 + v) * 64];
+        }
+        lds_barrier();   // read before the output tile below overwrites it
+    }
+    const bool owner = kh == 0;   // wavefronts that hold finished sums
     // C[i = token][n = row]: lane (row ln), register v holds token 8*(v/4) + 4*hl + v%4 of the group
     if (p.y_f32) {
+        if (!owner) return;
 #pragma unroll
         for (int j = 0; j < RJ; ++j)
 #pragma unroll
@@ -190,20 +231,22 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
     // fp16 output: the tile is turned in LDS (the operand buffers are free now; the loop's last
     // barrier has passed) so that it leaves in 16-byte pieces, 2 ROWS contiguous bytes per token,
     // instead of 2-byte pieces
-    _Float16* const yl = reinterpret_cast<_Float16*>(smem);   // [256 tokens][kGemmYLd]
+    _Float16* const yl = reinterpret_cast<_Float16*>(smem);   // [TOKS tokens][kGemmYLd]
+    if (owner) {
 #pragma unroll
-    for (int j = 0; j < RJ; ++j)
+        for (int j = 0; j < RJ; ++j)
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-                yl[(tg * 64 + t * 32 + 8 * (v >> 2) + 4 * hl + (v & 3)) * kGemmYLd + rg * (32 * RJ) + j * 32 + ln] =
-                    _Float16(acc[j][t][v]);
+                for (int v = 0; v < 16; ++v)
+                    yl[(tg * 64 + t * 32 + 8 * (v >> 2) + 4 * hl + (v & 3)) * kGemmYLd + rg * (32 * RJ) + j * 32 + ln] =
+                        _Float16(acc[j][t][v]);
+    }
     lds_barrier();
     __half* const y = static_cast<__half*>(p.y);
     constexpr int PIECES = ROWS / 8;   // 16-byte pieces per token
 #pragma unroll 4
-    for (int k = 0; k < 256 * PIECES / 512; ++k) {
+    for (int k = 0; k < TOKS * PIECES / 512; ++k) {
         const int idx = tid + 512 * k, tok = idx / PIECES, piece = idx % PIECES;
         const uint4 v = *reinterpret_cast<const uint4*>(yl + tok * kGemmYLd + piece * 8);
         if (tok0 + tok < p.batch && row0 + piece * 8 < p.out)
@@ -221,19 +264,30 @@ hipError_t launch_dense_zero(const LaunchArgs& a, hipStream_t st) {
 // Cost model of the product (microseconds, fitted to measurements): a round of workgroups takes
 // in x (a + b x the fraction of the 256 compute units that have a workgroup) - a partly filled
 // chip runs each tile faster (clock, shared caches) - with (a, b) = (0.0196, 0.0148) for 256-row
-// tiles and (0.0111, 0.0089) for 128-row tiles.  The launcher takes the cheaper tile height.
-static double tile_rounds_time_us(int out, int in, int batch, int rows) {
-    const int tiles = ((out + rows - 1) / rows) * ((batch + kGemmTokens - 1) / kGemmTokens);
-    const double a = rows == 128 ? 0.0111 : 0.0196, b = rows == 128 ? 0.0089 : 0.0148;
+// tiles, (0.0111, 0.0089) for 128-row tiles and (0.0068, 0.0032) for 128 x 128 tiles.  The
+// launcher takes the cheapest tile.
+enum GemmTile { kTile256 = 1, kTile128 = 2, kTile128x128 = 3 };
+static std::atomic<int> g_forced_tile{0};   // measurement hook: 0 = the estimate's choice
+void dense_force_tile(int tile) { g_forced_tile = tile; }
+
+static double tile_rounds_time_us(int out, int in, int batch, int tile) {
+    const int rows = tile == kTile256 ? 256 : 128, toks = tile == kTile128x128 ? 128 : kGemmTokens;
+    const int tiles = ((out + rows - 1) / rows) * ((batch + toks - 1) / toks);
+    const double a = tile == kTile256 ? 0.0196 : tile == kTile128 ? 0.0111 : 0.0068;
+    const double b = tile == kTile256 ? 0.0148 : tile == kTile128 ? 0.0089 : 0.0032;
     const int full = tiles / 256, rest = tiles % 256;
     return in * (full * (a + b) + (rest ? a + b * rest / 256.0 : 0.0));
 }
-bool dense_narrow_tiles(int out, int in, int batch) {
-    return tile_rounds_time_us(out, in, batch, 128) < tile_rounds_time_us(out, in, batch, 256);
+static int dense_tile(int out, int in, int batch) {
+    const int forced = g_forced_tile.load();
+    if (forced >= kTile256 && forced <= kTile128x128) return forced;
+    int best = kTile256;
+    for (int t = kTile128; t <= kTile128x128; ++t)
+        if (tile_rounds_time_us(out, in, batch, t) < tile_rounds_time_us(out, in, batch, best)) best = t;
+    return best;
 }
 double dense_time_us(int out, int in, int batch) {
-    const double n = tile_rounds_time_us(out, in, batch, 128), w = tile_rounds_time_us(out, in, batch, 256);
-    return n < w ? n : w;
+    return tile_rounds_time_us(out, in, batch, dense_tile(out, in, batch));
 }
 
 hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {
@@ -250,22 +304,27 @@ hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {
         return hipErrorInvalidValue;   // 32-bit byte offsets into x and the dense weight
     static std::atomic<bool> attr_set{false};   // setting the attribute twice is harmless
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<4>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<4, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<2>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<2, false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<2, true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int ntt = (p.batch + kGemmTokens - 1) / kGemmTokens;
-    const bool narrow = dense_narrow_tiles(p.out, p.in, p.batch);
-    const int nrt = (p.out + (narrow ? 128 : 256) - 1) / (narrow ? 128 : 256);
+    const int tile = dense_tile(p.out, p.in, p.batch);
+    const int rows = tile == kTile256 ? 256 : 128, toks = tile == kTile128x128 ? 128 : kGemmTokens;
+    const int ntt = (p.batch + toks - 1) / toks, nrt = (p.out + rows - 1) / rows;
     const unsigned wgs = unsigned(8 * ((nrt + 7) / 8) * ntt);
-    if (narrow)
-        hipLaunchKernelGGL(k_gemm<2>, dim3(wgs), dim3(512), kGemmLds, st, p);
+    if (tile == kTile128x128)
+        hipLaunchKernelGGL((k_gemm<2, true>), dim3(wgs), dim3(512), kGemmLds, st, p);
+    else if (tile == kTile128)
+        hipLaunchKernelGGL((k_gemm<2, false>), dim3(wgs), dim3(512), kGemmLds, st, p);
     else
-        hipLaunchKernelGGL(k_gemm<4>, dim3(wgs), dim3(512), kGemmLds, st, p);
+        hipLaunchKernelGGL((k_gemm<4, false>), dim3(wgs), dim3(512), kGemmLds, st, p);
     return hipGetLastError();
 }
 

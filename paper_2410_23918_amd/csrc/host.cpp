@@ -598,6 +598,7 @@ int bitstack_set_option(int option, int value) {
         case BITSTACK_OPT_DECODE_TILES: decode_tuning().tiles = value; return BITSTACK_OK;
         case BITSTACK_OPT_DECODE_KS_CHUNKS: decode_tuning().ks_chunks = value; return BITSTACK_OK;
         case BITSTACK_OPT_DECODE_EARLY: decode_tuning().early = value - 1; return BITSTACK_OK;
+        case BITSTACK_OPT_DENSE_TILE: dense_force_tile(value); return BITSTACK_OK;
         default: return BITSTACK_E_ARG;
     }
 }

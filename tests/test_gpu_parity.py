@@ -596,9 +596,11 @@ def test_restored_weight_matches_eq8(B, out, inn, n):
 @pytest.mark.parametrize("out,inn,n", [(1056, 768, 3), (96, 2048, 2)])
 def test_materialised_path_every_tile_variant(B, out, inn, n):
     """Restore + dense product against the oracle for batches on both sides of the product
-    kernel's tiles (32-token fragments, 64 tokens per wavefront, 256 per workgroup), with ragged
-    row tiles (out not a multiple of 256) and both output types; the two-step form (restore
-    once, multiply many times) gives the same bits as the combined call."""
+    kernel's tiles (32-token fragments, 64 tokens per wavefront, 128 or 256 per workgroup), with
+    ragged row tiles (out not a multiple of 128 or 256), both output types and each of the three
+    output tiles of the product forced in turn (256 x 256, 128 x 256, 128 x 128 with the columns
+    of a chunk split over the two halves of the workgroup), then the launcher's own choice; the
+    two-step form (restore once, multiply many times) gives the same bits as the combined call."""
     import torch
     st = synth_stack(3, out, inn, n)
     batches = (1, 31, 33, 64, 65, 255, 256, 257, 513)
@@ -609,15 +611,19 @@ def test_materialised_path_every_tile_variant(B, out, inn, n):
     for b in batches:
         xd = _to_dev(x[:b])
         for dt in (torch.float16, torch.float32):
-            y = ps.linear_materialised(xd, n, wd, out_dtype=dt)
-            torch.cuda.synchronize()
-            assert y.shape == (b, out)
-            err = O.relative_error(y.float().cpu().numpy(), ref[:b])
-            print(f"{out}x{inn} materialised B={b} {dt}: {err:.2e}", flush=True)
-            assert err <= TOL
-            y2 = ps.linear_dense(xd, wd, out_dtype=dt)
-            torch.cuda.synchronize()
-            assert torch.equal(y, y2)
+            for tile in (1, 2, 3, 0):
+                B.set_option(B.OPT_DENSE_TILE, tile)
+                try:
+                    y = ps.linear_materialised(xd, n, wd, out_dtype=dt)
+                    y2 = ps.linear_dense(xd, wd, out_dtype=dt)
+                    torch.cuda.synchronize()
+                finally:
+                    B.set_option(B.OPT_DENSE_TILE, 0)
+                assert y.shape == (b, out)
+                err = O.relative_error(y.float().cpu().numpy(), ref[:b])
+                print(f"{out}x{inn} materialised B={b} {dt}, product tile {tile or 'chosen'}: {err:.2e}", flush=True)
+                assert err <= TOL
+                assert torch.equal(y, y2)
     # a shorter prefix through the same scratch
     y = ps.linear_materialised(_to_dev(x[:70]), 1, wd)
     torch.cuda.synchronize()
@@ -710,7 +716,8 @@ def test_materialised_path_through_the_images_own_scratch(B):
     """No scratch lent: an image packed for many tokens carries max_batch x in fp16 of activation
     scratch (the weight-tile kernel's), which the materialising path uses for slabs of the dense
     weight.  Forced through the kernel selector: same bits as through a caller's scratch for the
-    whole matrix; the weight-tile kernel, which writes activations there, still works afterwards;
+    whole matrix when the dense product's tile is held fixed, the parity bound with the launcher's
+    own choice per slab; the weight-tile kernel, which writes activations there, still works afterwards;
     an image packed for at most 64 tokens has no such scratch and the selector is refused."""
     import torch
     out, inn, n = 2336, 1024, 3       # 1120 tokens of scratch = 1024 rows at a time: slabs of 1024, 1024, 288
@@ -722,11 +729,17 @@ def test_materialised_path_through_the_images_own_scratch(B):
     for b in (70, 1100):
         xd = _to_dev(x[:b])
         for dt in (torch.float16, torch.float32):
-            y_full = ps.linear_materialised(xd, n, full, out_dtype=dt)
+            B.set_option(B.OPT_DENSE_TILE, 3)
+            try:
+                y_full = ps.linear_materialised(xd, n, full, out_dtype=dt)
+                y_img = ps.linear_batched(xd, n, out_dtype=dt, kernel=B.KERNEL_MATERIALISE)
+                torch.cuda.synchronize()
+            finally:
+                B.set_option(B.OPT_DENSE_TILE, 0)
+            assert torch.equal(y_full, y_img), (b, dt)
             y_img = ps.linear_batched(xd, n, out_dtype=dt, kernel=B.KERNEL_MATERIALISE)
             y_tile = ps.linear_batched(xd, n, out_dtype=dt, kernel=B.KERNEL_PANEL)
             torch.cuda.synchronize()
-            assert torch.equal(y_full, y_img), (b, dt)
             for name, y in (("materialised through the image's scratch", y_img), ("batch kernel after it", y_tile)):
                 err = _report(f"{out}x{inn} B={b} {dt}, {name}", y.float().cpu().numpy(), ref[:b])
                 assert err <= TOL
@@ -742,9 +755,12 @@ def test_materialised_path_through_the_images_own_scratch(B):
 
 def test_materialised_path_in_row_slabs_through_a_small_scratch(B):
     """A scratch with room for fewer rows than the weight has: the weight is restored and multiplied
-    slab by slab through it.  Same bits as with a scratch for the whole matrix (the same kernels
-    do the same arithmetic per row), for a slab count that leaves a short last slab, both output
-    types, and through the library's own choice; a scratch below 1024 rows is refused."""
+    slab by slab through it.  With the dense product's output tile held fixed (each of its three
+    tiles in turn: 256 x 256, 128 x 256, 128 x 128 with the columns of a chunk split over two
+    halves of the workgroup) the bits are those of a scratch for the whole matrix -- the same
+    kernel does the same arithmetic per row -- for a slab count that leaves a short last slab and
+    both output types; with the launcher's own choice of tile per slab the result holds the
+    parity bound; a scratch below 1024 rows is refused."""
     import torch
     out, inn, n = 2336, 1024, 3       # 2336 = 2 x 1024 + 288: two full slabs and a ragged one
     st = synth_stack(3, out, inn, n)
@@ -757,13 +773,20 @@ def test_materialised_path_in_row_slabs_through_a_small_scratch(B):
         for b in (70, 600):
             xd = _to_dev(x[:b])
             for dt in (torch.float16, torch.float32):
-                y_full = ps.linear_materialised(xd, n, full, out_dtype=dt)
-                y_slab = ps.linear_materialised(xd, n, slab, out_dtype=dt)
-                torch.cuda.synchronize()
-                assert torch.equal(y_full, y_slab), (rows, b, dt)
-                err = O.relative_error(y_slab.float().cpu().numpy(), ref[:b])
-                print(f"{out}x{inn} scratch of {rows} rows, B={b} {dt}: {err:.2e}", flush=True)
-                assert err <= TOL
+                for tile in (1, 2, 3, 0):
+                    B.set_option(B.OPT_DENSE_TILE, tile)
+                    try:
+                        y_full = ps.linear_materialised(xd, n, full, out_dtype=dt)
+                        y_slab = ps.linear_materialised(xd, n, slab, out_dtype=dt)
+                        torch.cuda.synchronize()
+                    finally:
+                        B.set_option(B.OPT_DENSE_TILE, 0)
+                    if tile:
+                        assert torch.equal(y_full, y_slab), (rows, b, dt, tile)
+                    err = O.relative_error(y_slab.float().cpu().numpy(), ref[:b])
+                    print(f"{out}x{inn} scratch of {rows} rows, B={b} {dt}, product tile {tile or 'chosen per slab'}: "
+                          f"{err:.2e}", flush=True)
+                    assert err <= TOL
         assert bool((slab[rows * inn:] == 7.0).all())      # nothing written past the rows that fit
     slab = torch.empty((1024 * inn,), dtype=torch.float16, device="cuda:0")
     y0 = ps.linear_materialised(_to_dev(x[:70]), 0, slab)
