@@ -51,20 +51,6 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef short v2s __attribute__((ext_vector_type(2)));
 
-#ifdef BITSTACK_TRACE
-// Development build only (-DBITSTACK_TRACE): wavefronts 0 and 7 of the first 1024 workgroups note the
-// constant-rate clock at phase boundaries in LDS and copy the notes out when they leave.
-__device__ unsigned long long g_decode_trace[1024 * 128];
-extern "C" int bitstack_debug_decode_trace(unsigned long long* host, int n) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_decode_trace), size_t(n) * 8);
-}
-#define BS_TR(slot)                                                                              \
-    do {                                                                                         \
-        if (lane == 0 && (wave == 0 || wave == 7)) trace_lds[(wave ? 64 : 0) + (slot)] = wall_clock64(); \
-    } while (0)
-#else
-#define BS_TR(slot) do { } while (0)
-#endif
 
 namespace {
 
@@ -85,12 +71,7 @@ constexpr int kLdsAmaxStep = kLdsAmax + kDecodeMaxBlocksPerWg * 4;
 constexpr int kLdsColSums = kLdsAmaxStep + kDecodeMaxBlocksPerWg * kDecodeMaxRangeChunks * 8 * 2;
 constexpr int kLdsAmin = kLdsColSums + 3 * 32 * 4;
 constexpr int kLdsFlags = kLdsAmin + kDecodeMaxBlocksPerWg * 4;
-constexpr int kLdsTrace = kLdsFlags + 16;
-#ifdef BITSTACK_TRACE
-constexpr int kTraceBytes = 1024;
-#else
-constexpr int kTraceBytes = 0;
-#endif
+constexpr int kLdsBytes = kLdsFlags + 16;
 
 // maximum over each aligned group of 32 lanes, in all its lanes (values >= 0: compared as integers).
 // Four rotations inside the rows of 16 lanes, then one exchange between the two rows: no LDS atomics,
@@ -137,19 +118,8 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
     int* cs = reinterpret_cast<int*>(smem + kLdsColSums);                   // [3][32]
     int* amin_i = reinterpret_cast<int*>(smem + kLdsAmin);                  // [blocks]: smallest (chunk, class) maximum
     unsigned* flag = reinterpret_cast<unsigned*>(smem + kLdsFlags);         // [0] finisher flag, [1] max |x/s| bits
-#ifdef BITSTACK_TRACE
-    unsigned long long* trace_lds = reinterpret_cast<unsigned long long*>(smem + kLdsTrace);   // [2][64]
-#endif
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-#ifdef BITSTACK_TRACE
-    if (tid < 128) trace_lds[tid] = 0;
-    __syncthreads();
-#endif
-    BS_TR(0);
-#ifdef BITSTACK_TRACE
-    if (tid == 0) trace_lds[62] = __builtin_readcyclecounter();
-#endif
 
     // which stack of the group this workgroup serves (uniform)
     int gi = 0;
@@ -302,9 +272,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
             }
         }
     }
-    BS_TR(1);
     lds_barrier();   // P1: x/s table complete, tables cleared
-    BS_TR(2);
     {
         // exact max |V[j][r] * xs[j]| over the range for each of my blocks:
         // max_j |xs[j]| * max_r |V[j][r]|, the inner maximum stored at pack time (panel order)
@@ -344,7 +312,6 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
         for (int t0 = tid + kPreTasks * kThreads; t0 < tasks; t0 += kThreads) fold(t0, *vmax_ptr(t0));
     }
     lds_barrier();   // P2: maxima complete
-    BS_TR(3);
     // The quantiser multiplies in fp16: V[j][r] * (x[j]/s[j] * scale).  The second factor stays below
     // 8 / max_r |V[j][r]|, which only leaves fp16's range for channels whose V entries are all tiny
     // (< 1.3e-4) while x/s is huge; a block where that can happen takes the fp32 quantiser instead.
@@ -485,13 +452,10 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
     // first panel's V, the first sign units) do not share the compute unit's memory queue with them
     Raw raw_cur = load_raw(1);
     quantise(0, raw);
-    BS_TR(4);
 #pragma unroll
     for (int c = EARLY; c < kPieceChunks; ++c) request(0, c);
     __builtin_amdgcn_sched_barrier(0);
-    BS_TR(5);
     lds_barrier();   // P3: interval 0 staged
-    BS_TR(6);
 
     // ---------------------------------------------------------------- main loop
     v16i acc[R];
@@ -510,7 +474,6 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
             shift_lo = unsigned(__builtin_amdgcn_ballot_w64((my & 1) != 0));
             shift_hi = unsigned(__builtin_amdgcn_ballot_w64((my & 2) != 0));
         }
-        if (i < 12) BS_TR(8 + 4 * i);
         // column sums of block q + 2 start from zero: that buffer was last read in the epilogue of
         // block q - 1 (at least one barrier ago) and is first added to one barrier from now or later
         if (LAST && tid < 32) cs[((q + 2) % 3) * 32 + tid] = 0;
@@ -577,7 +540,6 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
             __builtin_amdgcn_sched_barrier(0);
             request(i + 1, c);
         }
-        if (i < 12) BS_TR(9 + 4 * i);
         if constexpr (LAST) {
             // epilogue: undo S = 2B - 1, weight by U, reduce over ranks.  Sums and column sums are on the
             // block's scale, 2^-E of the range's.
@@ -607,9 +569,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
                 yacc[tl] = fmaf(256.0f * sum[tl] + other, dq, yacc[tl]);   // meaningful in lanes 0..31
             }
         }
-        if (i < 12) BS_TR(10 + 4 * i);
         if (!late_wave && i + 1 < n_int) quantise(i + 1, raw_cur);
-        if (i < 12) BS_TR(11 + 4 * i);
         lds_barrier();
     };
     {
@@ -640,21 +600,14 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
     // counter bumped.  The finishing workgroup reads the rows back with agent-scope loads, which
     // miss in every cache that is not coherent across XCDs.  No cache-wide write-back or
     // invalidate is paid by anybody (those cost more than the whole sign stream of a block).
-    BS_TR(56);
     wait_all_vector_memory();
-    BS_TR(57);
     __syncthreads();
-    BS_TR(58);
     if (tid == 0) {
         const unsigned expected = unsigned(p.n_ks) * unsigned(p.n_bg);
         const unsigned old = __hip_atomic_fetch_add(&p.ctr[rs_i * kCounterStride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         *flag = (old + 1u == expected) ? 1u : 0u;
     }
     __syncthreads();
-    BS_TR(59);
-#ifdef BITSTACK_TRACE
-    const bool finishing = *flag != 0;
-#endif
     // Few partial rows per slab and one row per thread (R = 2): every thread adds up its row over all
     // slots, their loads in flight together, in slot order (fixed: the result does not depend on
     // which workgroup arrived last); no LDS, no barrier.  Measured 0.45 us faster than the general
@@ -733,13 +686,6 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
         }
         if (tid == 0) __hip_atomic_store(&p.ctr[rs_i * kCounterStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-#ifdef BITSTACK_TRACE
-    if (tid == 0) trace_lds[63] = __builtin_readcyclecounter();
-    BS_TR(61);
-    if (finishing) BS_TR(60);
-    __syncthreads();
-    if (tid < 128 && blockIdx.x < 1024) g_decode_trace[blockIdx.x * 128 + tid] = trace_lds[tid];
-#endif
 }
 
 
@@ -859,7 +805,7 @@ bool plan_decode(const LaunchArgs* a, int count, DecodePlan* best) {
 
 template <int R, int EARLY>
 hipError_t launch_variant(const KGroup& grp, unsigned wgs, hipStream_t st) {
-    const size_t smem = size_t(kLdsTrace) + kTraceBytes;
+    const size_t smem = size_t(kLdsBytes);
     static std::atomic<int> attr_state{0};   // per instantiation; setting the attribute twice is harmless
     if (attr_state.load(std::memory_order_acquire) == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_decode<R, EARLY>),
