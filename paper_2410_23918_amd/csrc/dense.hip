@@ -41,6 +41,9 @@ constexpr int kGemmTile = 256 * kGemmLd;    // fp16 per operand tile
 constexpr int kGemmLds = 2 * 2 * kGemmTile * 2;   // bytes: two buffers x {weight tile, activation tile}
 constexpr int kGemmYLd = 256 + 8;           // fp16 per LDS row of the output tile
 static_assert(256 * kGemmYLd * 2 <= kGemmLds, "the output tile reuses the operand buffers");
+constexpr int kGemmLdsSmall = kGemmLds / 2;       // the 128 x 128 variant: half-height tiles
+static_assert(128 * kGemmYLd * 2 <= kGemmLdsSmall && 4 * 64 * 64 * 4 <= kGemmLdsSmall,
+              "its output tile and the exchange of the column halves reuse the operand buffers");
 
 __global__ __launch_bounds__(256) void k_dense_zero(uint4* w, size_t n16) {
     const size_t i = size_t(blockIdx.x) * 256 + threadIdx.x;
@@ -56,14 +59,17 @@ __global__ __launch_bounds__(256) void k_dense_zero(uint4* w, size_t n16) {
 // 0-3 take the first 32 columns of every chunk, wavefronts 4-7 the other 32, and the two halves
 // are added through LDS after the loop.
 template <int RJ, bool KSPLIT>
-__global__ __launch_bounds__(512) void k_gemm(KParams p) {
+__global__ __launch_bounds__(512, KSPLIT ? 4 : 1) void k_gemm(KParams p) {
     static_assert(!KSPLIT || RJ == 2, "the 128 x 128 tile is built from 64 x 64 wavefront tiles");
     constexpr int ROWS = KSPLIT ? 128 : 64 * RJ;
     constexpr int TOKS = KSPLIT ? 128 : kGemmTokens;
     constexpr int STEPS = KSPLIT ? 2 : 4;   // 16-column steps of a chunk per wavefront
+    // fp16 per operand tile in LDS: 128 rows in the 128 x 128 variant, so that two of its workgroups
+    // (74 KB each, at most 128 registers per lane) fit a compute unit
+    constexpr int TILE = (KSPLIT ? 128 : 256) * kGemmLd;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     _Float16* const wl = reinterpret_cast<_Float16*>(smem);   // [buffer][256 rows][kGemmLd]
-    _Float16* const xl = wl + 2 * kGemmTile;                   // [buffer][256 tokens][kGemmLd]
+    _Float16* const xl = wl + 2 * TILE;                        // [buffer][256 tokens][kGemmLd]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hl = lane >> 5, ln = lane & 31;
@@ -99,7 +105,7 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
         return *reinterpret_cast<const uint4*>(base + off);
     };
     auto st16 = [&](_Float16* tile, int buf, int i, uint4 v) {
-        *reinterpret_cast<uint4*>(tile + buf * kGemmTile + dst + 64 * i * kGemmLd) = v;
+        *reinterpret_cast<uint4*>(tile + buf * TILE + dst + 64 * i * kGemmLd) = v;
     };
 #define BS_GEMM_LOAD(S, KC)                                                                \
     {                                                                                      \
@@ -136,10 +142,10 @@ __global__ __launch_bounds__(512) void k_gemm(KParams p) {
     const _Float16* const wfr = wl + (rg * (32 * RJ) + ln) * kGemmLd + 8 * hl + kh * 32;
     const _Float16* const xfr = xl + (tg * 64 + ln) * kGemmLd + 8 * hl + kh * 32;
     auto wfrag = [&](int buf, int s, int j) -> v8h {
-        return *reinterpret_cast<const v8h*>(wfr + buf * kGemmTile + j * 32 * kGemmLd + s * 16);
+        return *reinterpret_cast<const v8h*>(wfr + buf * TILE + j * 32 * kGemmLd + s * 16);
     };
     auto xfrag = [&](int buf, int s, int t) -> v8h {
-        return *reinterpret_cast<const v8h*>(xfr + buf * kGemmTile + t * 32 * kGemmLd + s * 16);
+        return *reinterpret_cast<const v8h*>(xfr + buf * TILE + t * 32 * kGemmLd + s * 16);
     };
 
     v16f acc[RJ][2];   // [row fragment][token group]
@@ -311,7 +317,7 @@ hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<2, true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsSmall);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
@@ -320,7 +326,7 @@ hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {
     const int ntt = (p.batch + toks - 1) / toks, nrt = (p.out + rows - 1) / rows;
     const unsigned wgs = unsigned(8 * ((nrt + 7) / 8) * ntt);
     if (tile == kTile128x128)
-        hipLaunchKernelGGL((k_gemm<2, true>), dim3(wgs), dim3(512), kGemmLds, st, p);
+        hipLaunchKernelGGL((k_gemm<2, true>), dim3(wgs), dim3(512), kGemmLdsSmall, st, p);
     else if (tile == kTile128)
         hipLaunchKernelGGL((k_gemm<2, false>), dim3(wgs), dim3(512), kGemmLds, st, p);
     else
