@@ -337,7 +337,9 @@ static int choose_kernel(const Geometry& g, int batch, int n_loaded, size_t work
     int kernel = t_decode <= t_panel ? BITSTACK_KERNEL_DECODE : BITSTACK_KERNEL_PANEL;
     const double t_best = t_decode <= t_panel ? t_decode : t_panel;
     const int slab = slab_rows(g, workspace_bytes);
-    if (n_loaded <= restore_max_blocks() && slab > 0) {
+    // (the dense product addresses x and a slab of the dense weight with 32-bit byte offsets)
+    const bool dense_ok = size_t(batch) * g.in * 2 <= 0xffffffffull && size_t(slab) * g.in * 2 <= 0xffffffffull;
+    if (n_loaded <= restore_max_blocks() && slab > 0 && dense_ok) {
         // per slab of rows: restore (~6.1 T weight-element-blocks/s) + product, ~10 us fixed each
         double t_mat = 0.0;
         for (int r0 = 0; r0 < g.out; r0 += slab) {

@@ -173,6 +173,9 @@ def test_kernel_choice_is_host_logic():
     assert B.choose_kernel(14336, 4096, 16, 2048, 128, 16, big) == B.KERNEL_PANEL
     assert B.choose_kernel(14336, 4096, 16, 2048, 512, 16, big) == B.KERNEL_PANEL
     assert B.choose_kernel(14336, 4096, 16, 2048, 1024, 16, big) == B.KERNEL_MATERIALISE
+    # the dense product addresses x with 32-bit byte offsets: a batch beyond that stays with the weight-tile kernel
+    assert B.choose_kernel(4096, 8192, 4, 3000, 3000, 4, 0) == B.KERNEL_MATERIALISE
+    assert B.choose_kernel(4096, 8192, 4, 300000, 300000, 4, 0) == B.KERNEL_PANEL
     L = B.lib()
     assert L.bitstack_choose_kernel(4096, 100, 16, 1, 1, 1, 0) == -2
     assert L.bitstack_choose_kernel(4096, 4096, 16, 8, 9, 1, 0) == -3
