@@ -265,9 +265,10 @@ def batch_table(B, torch, dev, n):
 
 def decompose_table(B, torch, dev, iterations=16):
     """The decomposition on the device (bitstack_decompose): time per residual block at the 4096x4096
-    and 14336x4096 shapes.  Algorithmic bytes per block: the fp32 residual is read once by each of
-    the 2 * iterations + 2 tall products and by the sign packing, and read and written once by the
-    residual update."""
+    and 14336x4096 shapes.  Bytes per block as the kernels move them: the fp32 residual is read by
+    the sign packing, by the conversion to bf16 (which writes |R| and its transpose), by the
+    Rayleigh-Ritz product, and read and written by the residual update (5 x 4 bytes per element);
+    the 2 * iterations + 1 tall products of the power rounds read one bf16 copy each."""
     from workloads import synth as W
     rows = []
     for cfg, (o, i), nblk in ((2, (4096, 4096), 4), (3, (14336, 4096), 2)):
@@ -281,10 +282,10 @@ def decompose_table(B, torch, dev, iterations=16):
         t0 = time.perf_counter()
         sw, U, V = B.decompose(Wd, s, nblk, iterations=iterations)   # synchronises before returning
         ms = (time.perf_counter() - t0) * 1e3 / nblk
-        bytes_per_block = (2 * iterations + 2 + 1 + 2) * o * i * 4
+        bytes_per_block = (5 * 4 + (2 + 2 * iterations + 1) * 2) * o * i
         gbs = bytes_per_block / ms / 1e6
         log(f"[bench] decomposition on the device {o}x{i}, {iterations} iterations: {ms:.1f} ms per block, "
-            f"{gbs:.0f} GB/s of residual traffic ({gbs / HBM_PEAK_GBS * 100:.1f}% of 8 TB/s)")
+            f"{gbs:.0f} GB/s of residual traffic, fp32 and bf16 passes ({gbs / HBM_PEAK_GBS * 100:.1f}% of 8 TB/s)")
         rows.append({"shape": f"{o}x{i}", "iterations": iterations, "ms_per_block": round(ms, 2),
                      "residual_GBs": round(gbs, 1)})
         del Wd, sw, U, V

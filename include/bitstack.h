@@ -351,8 +351,9 @@ int bitstack_linear_materialised(const void* x, int batch, const bitstack_weight
  *     rounded to fp16;   R_{i+1} = R_i - S_i (.) (U_i V_i^T)  with the factors as stored.
  * The singular triplets come from a block power (subspace) iteration with k + 16 columns and
  * `iterations` rounds (0 = 16; one round applies |R| |R|^T once; the residual norm after a block
- * exceeds the exact truncation's by ~3e-4 / 7e-5 / 2e-5 / 8e-6 relative with 8 / 12 / 16 / 20 rounds) followed by a Rayleigh-Ritz step, in fp32 (small Gram and
- * eigenvalue problems in fp64).
+ * exceeds the exact truncation's by ~3e-4 / 7e-5 / 2e-5 / 8e-6 relative with 8 / 12 / 16 / 20 rounds) followed by a Rayleigh-Ritz step.  The rounds multiply
+ * bf16 copies of |R| on the matrix cores with fp32 sums; the Rayleigh-Ritz step, which fixes the
+ * factors, works on the fp32 residual (small Gram, Cholesky and eigenvalue problems in fp64).
  *   W: device fp32 [out][in] row-major, 16-byte aligned (not modified).
  *   s: HOST fp32 [in], every entry finite and > 0 (BITSTACK_E_SCALE otherwise); copied to the
  *   device by a copy enqueued on stream: keep it valid and unchanged until the stream has passed it.
@@ -361,7 +362,8 @@ int bitstack_linear_materialised(const void* x, int batch, const bitstack_weight
  *   bitstack_pack_blocks once copied to the host.
  *   workspace: device, caller-owned, 256-byte aligned, at least
  *   bitstack_decompose_workspace_bytes(out, in, k) bytes (BITSTACK_E_BUFSIZE otherwise); it holds
- *   the fp32 residual (out x in x 4 bytes) and the iteration's tall matrices.
+ *   the fp32 residual (out x in x 4 bytes), two bf16 copies of its absolute values (2 x out x
+ *   in x 2 bytes) and the iteration's tall matrices.
  * Asynchronous, allocates nothing.  The factors of a block are unique only
  * up to the sign of each column pair and rotations inside clusters of equal singular values;
  * U_i V_i^T and the residual norms are what can be compared between implementations. */

@@ -6,10 +6,11 @@
 //     split of Eq. 2, factors rounded to fp16),   R_{i+1} = R_i - S_i (.) (U_i V_i^T)   (Eq. 6)
 //
 // "SVD" is a block power (subspace) iteration with k + 16 columns followed by a Rayleigh-Ritz
-// step; any method that returns the leading triplets is a valid reading.  Everything is fp32 on
-// the vector ALUs except the 32 x 32 Gram / eigenvalue problems, which are fp64.  The two tall
-// products per iteration, |R| X and |R|^T Y, read the fp32 residual once each and are bound by
-// that read; |.| is applied as the residual is loaded, the sign matrix is never materialised.
+// step; any method that returns the leading triplets is a valid reading.  The two tall products
+// per round, |R| X and |R|^T Y, run on the bf16 matrix cores from bf16 copies of |R| (written once
+// per block, row-major and transposed); the product of the Rayleigh-Ritz step, which fixes U and V,
+// reads the fp32 residual (|.| applied as it is loaded); sums are fp32, the 32 x 32 Gram /
+// Cholesky / eigenvalue problems fp64.  The sign matrix is never materialised.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
@@ -38,6 +39,12 @@ __global__ __launch_bounds__(256) void k_dc_random(float* X, size_t total, unsig
     unsigned h = unsigned(i) * 2654435761u ^ seed;
     h ^= h >> 16; h *= 0x85ebca6bu; h ^= h >> 13; h *= 0xc2b2ae35u; h ^= h >> 16;
     X[i] = float(int(h >> 8) - (1 << 23)) * (1.0f / float(1 << 23));
+}
+
+// fp32 -> bf16, round to nearest even (the residual is finite)
+__device__ __forceinline__ unsigned short bf16_of(float x) {
+    const unsigned u = __float_as_uint(x);
+    return (unsigned short)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
 // canonical sign words of the residual: bit b of word w of a row = (R[row][32 w + b] >= 0),
@@ -118,6 +125,96 @@ __global__ __launch_bounds__(256) void k_dc_mul(const float* R, const float* X, 
     }
 }
 
+// |R| as bf16, twice: Rh[o][j] and its transpose RhT[j][o], for the power rounds' tall products
+// (half the bytes of the fp32 residual, and a reduction index that is contiguous in memory for
+// either orientation).  64 x 64 tiles through LDS.
+__global__ __launch_bounds__(256) void k_dc_half(const float* R, unsigned short* Rh, unsigned short* RhT, int out, int in) {
+    __shared__ unsigned short Ts[64][64 + 2];
+    const int tid = threadIdx.x;
+    const int o0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int idx = tid + 256 * i, r = idx >> 4, q = idx & 15;   // row o0 + r, columns j0 + 4 q ..
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (o0 + r < out) v = *reinterpret_cast<const float4*>(R + size_t(o0 + r) * in + j0 + 4 * q);
+        const unsigned short h[4] = {bf16_of(fabsf(v.x)), bf16_of(fabsf(v.y)), bf16_of(fabsf(v.z)), bf16_of(fabsf(v.w))};
+        if (o0 + r < out)
+            *reinterpret_cast<uint2*>(Rh + size_t(o0 + r) * in + j0 + 4 * q) =
+                make_uint2(unsigned(h[0]) | unsigned(h[1]) << 16, unsigned(h[2]) | unsigned(h[3]) << 16);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) Ts[4 * q + e][r] = h[e];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int idx = tid + 256 * i, c = idx >> 4, q = idx & 15;   // column j0 + c, rows o0 + 4 q ..
+        if (o0 + 4 * q < out)   // out is a multiple of 32: a group of four rows is inside or outside as a whole
+            *reinterpret_cast<uint2*>(RhT + size_t(j0 + c) * out + o0 + 4 * q) =
+                make_uint2(unsigned(Ts[c][4 * q]) | unsigned(Ts[c][4 * q + 1]) << 16,
+                           unsigned(Ts[c][4 * q + 2]) | unsigned(Ts[c][4 * q + 3]) << 16);
+    }
+}
+
+// The power rounds' tall products on the bf16 matrix cores: P[slice][m][c] = sum_{k in slice}
+// A[m][k] X[k][c] with A = Rh (M = out, K = in) or RhT (M = in, K = out), row-major with K
+// contiguous, X (K x kL, fp32) rounded to bf16 as it is staged.  A perturbation of |R| and of the
+// iterate of 2^-9 relative per element turns the subspace the rounds converge to by far less than
+// the oversampling and the Rayleigh-Ritz step, which works on the fp32 residual, absorb.  A
+// workgroup (4 wavefronts) owns 128 output indices and one slice of the reduction range, 64
+// reduction indices per LDS stage (K is a multiple of 32: a last half stage is filled with zeros).
+constexpr int kHChunk = 64;
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+__global__ __launch_bounds__(256) void k_dc_mulh(const unsigned short* A, const float* X, float* P, int M, int K,
+                                                 int chunks_per_slice) {
+    __shared__ __attribute__((aligned(16))) unsigned short As[kDcTile][kHChunk + 8];   // [m][k]
+    __shared__ __attribute__((aligned(16))) unsigned short Xs[kL][kHChunk + 8];        // [c][k]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hl = lane >> 5, ln = lane & 31;
+    const int m0 = blockIdx.x * kDcTile;
+    const int chunks = (K + kHChunk - 1) / kHChunk;
+    const int c_begin = blockIdx.y * chunks_per_slice;
+    const int c_end = min(chunks, c_begin + chunks_per_slice);
+    v16f acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    for (int ch = c_begin; ch < c_end; ++ch) {
+        const int k0 = ch * kHChunk;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = tid + 256 * i, m = idx >> 3, q = idx & 7;   // row m0 + m, reduction indices k0 + 8 q ..
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (m0 + m < M && k0 + 8 * q < K) v = *reinterpret_cast<const uint4*>(A + size_t(m0 + m) * K + k0 + 8 * q);
+            *reinterpret_cast<uint4*>(&As[m][8 * q]) = v;
+        }
+        {
+            const int kk = tid >> 2, cq = tid & 3;   // reduction index k0 + kk, columns 8 cq ..
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+            if (k0 + kk < K) {
+                a = *reinterpret_cast<const float4*>(X + size_t(k0 + kk) * kL + 8 * cq);
+                b = *reinterpret_cast<const float4*>(X + size_t(k0 + kk) * kL + 8 * cq + 4);
+            }
+            const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) Xs[8 * cq + e][kk] = bf16_of(x[e]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < kHChunk / 16; ++s) {
+            const v8bf a = *reinterpret_cast<const v8bf*>(&As[wave * 32 + ln][16 * s + 8 * hl]);
+            const v8bf b = *reinterpret_cast<const v8bf*>(&Xs[ln][16 * s + 8 * hl]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // D[i = output index][n = column]: lane (column ln), register v holds index 8*(v/4) + 4*hl + v%4
+    float* Ps = P + size_t(blockIdx.y) * M * kL;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int m = m0 + wave * 32 + 8 * (v >> 2) + 4 * hl + (v & 3);
+        if (m < M) Ps[size_t(m) * kL + ln] = acc[v];
+    }
+}
+
 // Y = sum of the product's slices (written out) and this workgroup's part of Y^T Y in fp64:
 // 128 rows of Y (m x kL) per workgroup in four stages of 32, every thread four columns of one row
 // with the loads of all slices in flight together.  The parts are added up in a fixed order by
@@ -183,92 +280,75 @@ __device__ __forceinline__ void gram_sum(const double* Gpart, int parts, double 
     Gs[e / kL][e % kL] = acc;
 }
 
-// the Gram matrix from its parts, in a fixed order, into LDS (256 threads, four entries each)
-__device__ __forceinline__ void gram_sum4(const double* Gpart, int parts, double (*Gs)[kL + 1]) {
-    const int e0 = threadIdx.x * 4;
-    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
-    typedef double d2 __attribute__((ext_vector_type(2)));
-    int p = 0;
-    for (; p + 4 <= parts; p += 4) {   // four parts' loads in flight together; the order of the additions is fixed
-        d2 lo[4], hi[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const d2* src = reinterpret_cast<const d2*>(Gpart + size_t(p + u) * (kL * kL) + e0);
-            lo[u] = src[0];
-            hi[u] = src[1];
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            a0 += lo[u][0]; a1 += lo[u][1]; a2 += hi[u][0]; a3 += hi[u][1];
-        }
-    }
-    for (; p < parts; ++p) {
-        const double* src = Gpart + size_t(p) * (kL * kL) + e0;
-        a0 += src[0]; a1 += src[1]; a2 += src[2]; a3 += src[3];
-    }
-    const int row = e0 / kL, col = e0 % kL;
-    Gs[row][col] = a0; Gs[row][col + 1] = a1; Gs[row][col + 2] = a2; Gs[row][col + 3] = a3;
-}
-
-// G = C^T C (Cholesky, C upper triangular), T = C^-1, so that Y T has orthonormal columns.
-// 256 threads add up the parts of G; then 32 of them factorise in fp64: thread t keeps row t of
-// the lower factor in registers, finished rows are published through LDS (one barrier per column).
-__global__ __launch_bounds__(256) void k_dc_chol_inv(const double* Gpart, int parts, float* T) {
+// G = L L^T (Cholesky, L lower triangular) so that Q = Y L^-T has orthonormal columns; the kernel that
+// applies it solves Q L^T = Y row by row.  Right-looking, one thread per matrix entry, fp64: at step
+// j the threads of column j publish their entries (final after the updates of the earlier steps)
+// and thread (j, j) the reciprocal of the pivot and its square root; after one barrier column j of
+// L is raw / sqrt(pivot) and every entry below and right of the pivot takes its rank-one update.
+// No chain of dependent operations longer than one division per step.
+//   Lout: kL x kL fp32, row-major, L[r][c] for c < r, and 1 / L[r][r] on the diagonal (what the
+//   substitution multiplies by); all zero for an all-zero Y (no direction to normalise: Q = 0).
+__global__ __launch_bounds__(kSmallThreads) void k_dc_chol(const double* Gpart, int parts, float* Lout) {
     __shared__ double Gs[kL][kL + 1];
-    __shared__ double Lr[kL][kL + 1];
-    const int t = threadIdx.x;
-    gram_sum4(Gpart, parts, Gs);
-    __syncthreads();
-    if (t >= 64) return;   // the factorisation is one wavefront's work; its barriers then cost little
-    double a[kL];
-    if (t < kL) {
-        Lr[t][t] = Gs[t][t];   // the diagonal, for the trace
-#pragma unroll
-        for (int c = 0; c < kL; ++c) a[c] = Gs[t][c];
-    }
+    __shared__ double colj[2][kL];
+    __shared__ double piv[2][2];
+    const int t = threadIdx.x, r = t / kL, c = t % kL;
+    gram_sum(Gpart, parts, Gs);
     __syncthreads();
     double tr = 0.0;
-    for (int c = 0; c < kL; ++c) tr += Lr[c][c];
-    if (!(tr > 0.0)) {   // Y = 0 (an all-zero residual): no direction to normalise, Q = 0
-        if (t < kL)
-            for (int c = 0; c < kL; ++c) T[t * kL + c] = 0.f;
+#pragma unroll
+    for (int k = 0; k < kL; ++k) tr += Gs[k][k];
+    if (!(tr > 0.0)) {   // uniform over the workgroup
+        Lout[t] = 0.f;
         return;
     }
     // a tiny ridge keeps the factorisation defined if the columns are (numerically) dependent
     const double ridge = tr * 1e-13;
-    __syncthreads();
-#pragma unroll
+    double a = Gs[r][c] + (r == c ? ridge : 0.0);
+    double mine = 0.0;   // my entry of L (r > c), or 1 / L[r][r]
     for (int j = 0; j < kL; ++j) {
-        if (t == j) {
-            double d = a[j] + ridge;
-#pragma unroll
-            for (int k = 0; k < j; ++k) d -= a[k] * a[k];
-            a[j] = sqrt(d > 0.0 ? d : ridge);
-#pragma unroll
-            for (int k = 0; k <= j; ++k) Lr[j][k] = a[k];
+        const int b = j & 1;
+        if (c == j && r >= j) {
+            colj[b][r] = a;
+            if (r == j) {
+                const double d = a > 0.0 ? a : ridge;
+                const double inv = 1.0 / d;
+                piv[b][0] = inv;
+                piv[b][1] = sqrt(inv);
+            }
         }
         __syncthreads();
-        if (t > j && t < kL) {
-            double v = a[j];
-#pragma unroll
-            for (int k = 0; k < j; ++k) v -= a[k] * Lr[j][k];
-            a[j] = v / Lr[j][j];
-        }
+        if (c == j && r >= j) mine = r == j ? piv[b][1] : a * piv[b][1];   // 1 / sqrt(d), or a_rj / sqrt(d)
+        if (c > j && r >= c) a -= colj[b][r] * colj[b][c] * piv[b][0];
     }
+    Lout[t] = r >= c ? float(mine) : 0.f;
+}
+
+// Q L^T = Y for every row of Y (m x kL), L as k_dc_chol leaves it (reciprocal pivots on the diagonal):
+// q_c = (y_c - sum_{i < c} q_i L[c][i]) / L[c][c].  One row per thread, L in LDS (all lanes read the
+// same entry: a broadcast).  Y and Q may be the same array.
+__global__ __launch_bounds__(256) void k_dc_solve(const float* Y, const float* Lg, float* Q, int m) {
+    __shared__ __attribute__((aligned(16))) float Ls[kL][kL];
+    for (int idx = threadIdx.x; idx < kL * kL; idx += 256) Ls[idx / kL][idx % kL] = Lg[idx];
     __syncthreads();
-    // column t of L^-1 by forward substitution (in registers), T = C^-1 = (L^-1)^T
-    if (t < kL) {
-        double li[kL];
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= m) return;
+    float q[kL];
 #pragma unroll
-        for (int r = 0; r < kL; ++r) {
-            double v = (r == t) ? 1.0 : 0.0;
-#pragma unroll
-            for (int k = 0; k < r; ++k) v -= (k >= t) ? Lr[r][k] * li[k] : 0.0;
-            li[r] = (r < t) ? 0.0 : v / Lr[r][r];
-        }
-#pragma unroll
-        for (int c = 0; c < kL; ++c) T[t * kL + c] = float(li[c]);
+    for (int g = 0; g < kL / 4; ++g) {
+        const float4 v = *reinterpret_cast<const float4*>(Y + size_t(r) * kL + 4 * g);
+        q[4 * g] = v.x; q[4 * g + 1] = v.y; q[4 * g + 2] = v.z; q[4 * g + 3] = v.w;
     }
+#pragma unroll
+    for (int c = 0; c < kL; ++c) {
+        float v = q[c];
+#pragma unroll
+        for (int i = 0; i < c; ++i) v = fmaf(-q[i], Ls[c][i], v);
+        q[c] = v * Ls[c][c];
+    }
+#pragma unroll
+    for (int g = 0; g < kL / 4; ++g)
+        *reinterpret_cast<float4*>(Q + size_t(r) * kL + 4 * g) = make_float4(q[4 * g], q[4 * g + 1], q[4 * g + 2], q[4 * g + 3]);
 }
 
 // Q[r][c] = sum_i Y[r][i] T[i][c], c < NC; fp32 or fp16 (round to nearest even) output
@@ -436,6 +516,7 @@ __global__ __launch_bounds__(256) void k_dc_update(float* R, const __half* U, co
 size_t decompose_workspace_bytes(int out, int in, int slices) {
     const size_t mx = size_t(out > in ? out : in);
     size_t b = align256(size_t(out) * in * 4);               // R
+    b += 2 * align256(size_t(out) * in * 2);                 // |R| as bf16 and its transpose
     b += 2 * align256(size_t(out) * kL * 4);                 // Y, Q (out side)
     b += 2 * align256(size_t(in) * kL * 4);                  // Z, Qz (in side)
     b += align256(size_t(slices) * mx * kL * 4);             // partial products
@@ -462,6 +543,8 @@ hipError_t launch_decompose(const float* W, const float* s, int out, int in, int
         return p;
     };
     float* R = reinterpret_cast<float*>(take(size_t(out) * in * 4));
+    unsigned short* Rh = reinterpret_cast<unsigned short*>(take(size_t(out) * in * 2));
+    unsigned short* RhT = reinterpret_cast<unsigned short*>(take(size_t(out) * in * 2));
     float* Y = reinterpret_cast<float*>(take(size_t(out) * kL * 4));
     float* Q = reinterpret_cast<float*>(take(size_t(out) * kL * 4));
     float* Z = reinterpret_cast<float*>(take(size_t(in) * kL * 4));
@@ -476,27 +559,35 @@ hipError_t launch_decompose(const float* W, const float* s, int out, int in, int
     hipLaunchKernelGGL(k_dc_scale, dim3(unsigned((total + 255) / 256)), dim3(256), 0, st, W, s, R, total, in);
 
     // P = slices of |R| X  (X: in x kL)  or of  |R|^T X  (X: out x kL)
-    auto mul = [&](bool trans, const float* X) {
+    // (exact: from the fp32 residual; otherwise from its bf16 copies, which the power rounds use)
+    auto mul = [&](bool trans, const float* X, bool exact) {
         const int M = trans ? in : out, K = trans ? out : in;
-        const int chunks = K / kDcChunk;
-        const int per = (chunks + slices - 1) / slices;
         dim3 grid((M + kDcTile - 1) / kDcTile, slices);
-        if (trans)
-            hipLaunchKernelGGL(k_dc_mul<true>, grid, dim3(256), 0, st, R, X, P, out, in, per);
-        else
-            hipLaunchKernelGGL(k_dc_mul<false>, grid, dim3(256), 0, st, R, X, P, out, in, per);
+        if (exact) {
+            const int chunks = K / kDcChunk;
+            const int per = (chunks + slices - 1) / slices;
+            if (trans)
+                hipLaunchKernelGGL(k_dc_mul<true>, grid, dim3(256), 0, st, R, X, P, out, in, per);
+            else
+                hipLaunchKernelGGL(k_dc_mul<false>, grid, dim3(256), 0, st, R, X, P, out, in, per);
+        } else {
+            const int chunks = (K + kHChunk - 1) / kHChunk;
+            const int per = (chunks + slices - 1) / slices;
+            hipLaunchKernelGGL(k_dc_mulh, grid, dim3(256), 0, st, trans ? RhT : Rh, X, P, M, K, per);
+        }
     };
     // the product in P, added up into raw (m x kL), columns made orthonormal into dst: Cholesky
-    // QR with the Gram matrix in fp64; a second pass (twice = orthonormal to rounding) where asked
+    // QR with the Gram matrix in fp64 (factor, then a triangular solve per row); a second pass
+    // (twice = orthonormal to rounding) where asked
     auto orth = [&](float* raw, float* dst, int m, bool twice) {
         const int parts = (m + kGramRows - 1) / kGramRows;
         hipLaunchKernelGGL(k_dc_gram, dim3(parts), dim3(256), 0, st, P, slices, raw, m, G);
-        hipLaunchKernelGGL(k_dc_chol_inv, dim3(1), dim3(256), 0, st, G, parts, T);
-        hipLaunchKernelGGL((k_dc_apply<kL, false>), dim3((m + 255) / 256), dim3(256), 0, st, raw, T, dst, m);
+        hipLaunchKernelGGL(k_dc_chol, dim3(1), dim3(kSmallThreads), 0, st, G, parts, T);
+        hipLaunchKernelGGL(k_dc_solve, dim3((m + 255) / 256), dim3(256), 0, st, raw, T, dst, m);
         if (twice) {
             hipLaunchKernelGGL(k_dc_gram, dim3(parts), dim3(256), 0, st, dst, 1, raw, m, G);
-            hipLaunchKernelGGL(k_dc_chol_inv, dim3(1), dim3(256), 0, st, G, parts, T);
-            hipLaunchKernelGGL((k_dc_apply<kL, false>), dim3((m + 255) / 256), dim3(256), 0, st, raw, T, dst, m);
+            hipLaunchKernelGGL(k_dc_chol, dim3(1), dim3(kSmallThreads), 0, st, G, parts, T);
+            hipLaunchKernelGGL(k_dc_solve, dim3((m + 255) / 256), dim3(256), 0, st, raw, T, dst, m);
         }
     };
 
@@ -506,20 +597,22 @@ hipError_t launch_decompose(const float* W, const float* s, int out, int in, int
         __half* Vi = V + size_t(i) * in * kRank;
         const size_t waves = size_t(out) * (in / 64);
         hipLaunchKernelGGL(k_dc_signs, dim3(unsigned((waves + 3) / 4)), dim3(256), 0, st, R, sw, out, in);
+        if (iters > 0)
+            hipLaunchKernelGGL(k_dc_half, dim3(in / 64, (out + 63) / 64), dim3(256), 0, st, R, Rh, RhT, out, in);
         // start: random X (in x kL) -> Y = |R| X -> Q
         hipLaunchKernelGGL(k_dc_random, dim3(unsigned((size_t(in) * kL + 255) / 256)), dim3(256), 0, st, Qz,
                            size_t(in) * kL, 0x9e3779b9u * unsigned(i + 1));
-        mul(false, Qz);
+        mul(false, Qz, iters == 0);
         orth(Y, Q, out, iters == 0);
         // one round = |R| |R|^T applied to Q; only Q is made orthonormal again (the product in
         // between spreads the columns' lengths by sigma_0 / sigma_31 ~ 30, far inside fp32)
         for (int it = 0; it < iters; ++it) {
-            mul(true, Q);
+            mul(true, Q, false);
             hipLaunchKernelGGL(k_dc_gram, dim3((in + kGramRows - 1) / kGramRows), dim3(256), 0, st, P, slices, Z, in, static_cast<double*>(nullptr));
-            mul(false, Z);
+            mul(false, Z, false);
             orth(Y, Q, out, it == iters - 1);
         }
-        mul(true, Q);
+        mul(true, Q, true);   // the Rayleigh-Ritz step sees the fp32 residual
         hipLaunchKernelGGL(k_dc_gram, dim3((in + kGramRows - 1) / kGramRows), dim3(256), 0, st, P, slices, Z, in, G);
         hipLaunchKernelGGL(k_dc_ritz, dim3(1), dim3(kSmallThreads), 0, st, G, (in + kGramRows - 1) / kGramRows, Tu, Tv, kRank);
         hipLaunchKernelGGL((k_dc_apply<kRank, true>), dim3((out + 255) / 256), dim3(256), 0, st, Q, Tu, Ui, out);
