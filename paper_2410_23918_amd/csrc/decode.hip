@@ -947,7 +947,14 @@ static double decode_launch_time_us(const Geometry& g, int m, int n_loaded) {
         a[i].y_f32 = false;
     }
     DecodePlan pl;
-    return plan_decode(a, m, &pl) ? pl.us : 0.0;
+    if (!plan_decode(a, m, &pl)) return 0.0;
+    // The work-split estimate prices intervals whose sign units are there; big stacks are bound by the
+    // stream instead: ~4.4 TB/s from memory for one token, and every further member streams the
+    // units again, from the L2s and the last-level cache at best (measured 2.7-3.9 TB/s over all
+    // members' bytes), after ~9 us of the fixed part that overlaps with nothing.
+    const double bytes = double(m) * n_loaded * (double(g.out) * g.in / 8.0);
+    const double stream_us = 9.0 + bytes / (m == 1 ? 4.4e6 : 3.3e6);
+    return pl.us > stream_us ? pl.us : stream_us;
 }
 
 // How a small batch is cut into launches of one to four tokens: the cut with the smallest

@@ -293,7 +293,11 @@ static int dense_tile(int out, int in, int batch) {
     return best;
 }
 double dense_time_us(int out, int in, int batch) {
-    return tile_rounds_time_us(out, in, batch, dense_tile(out, in, batch));
+    // never below one pass over both operands at ~3.5 TB/s (few tokens: every tile reads its own rows
+    // of the weight once and nothing is reused)
+    const double t = tile_rounds_time_us(out, in, batch, dense_tile(out, in, batch));
+    const double stream = (double(out) + batch) * in * 2.0 / 3.5e6;
+    return t > stream ? t : stream;
 }
 
 hipError_t launch_dense(const LaunchArgs& a, hipStream_t st) {

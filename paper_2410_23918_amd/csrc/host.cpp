@@ -340,11 +340,11 @@ static int choose_kernel(const Geometry& g, int batch, int n_loaded, size_t work
     // (the dense product addresses x and a slab of the dense weight with 32-bit byte offsets)
     const bool dense_ok = size_t(batch) * g.in * 2 <= 0xffffffffull && size_t(slab) * g.in * 2 <= 0xffffffffull;
     if (n_loaded <= restore_max_blocks() && slab > 0 && dense_ok) {
-        // per slab of rows: restore (~6.1 T weight-element-blocks/s) + product, ~10 us fixed each
+        // per slab of rows: restore + product, two launches (~4 us each between kernels of one stream)
         double t_mat = 0.0;
         for (int r0 = 0; r0 < g.out; r0 += slab) {
             const int rows = slab < g.out - r0 ? slab : g.out - r0;
-            t_mat += 10.0 + double(rows) * g.in * n_loaded / 6.1e6 + 10.0 + dense_time_us(rows, g.in, batch);
+            t_mat += 8.0 + restore_time_us(rows, g.in, n_loaded, nullptr) + dense_time_us(rows, g.in, batch);
         }
         if (t_mat < t_best) kernel = BITSTACK_KERNEL_MATERIALISE;
     }

@@ -64,6 +64,7 @@ hipError_t launch_dense(const LaunchArgs& a, hipStream_t st);
 // k_gemm's tile choice (128-row tiles or 256-row ones) and its estimated duration
 void dense_force_tile(int tile);   // measurement hook: 1 = 256-row tiles, 2 = 128-row tiles, 3 = 128 x 128 tiles, 0 = the estimate's choice
 double dense_time_us(int out, int in, int batch);
+double restore_time_us(int rows, int in, int n_loaded, int* slices_out);   // and the column slices its launcher takes
 // estimated durations of the two batch kernels (microseconds); launch_panel takes the cheaper one
 // for 33..64 tokens
 double fused_time_us(int out, int in, int batch, int n_loaded, int part_slots);

@@ -933,6 +933,27 @@ static hipError_t launch_tile(const KParams& p, hipStream_t st) {
 }
 
 // W' diag(1/s) of the loaded prefix as a dense fp16 matrix [out][in] (row-major) at a.wdense.
+// Estimated duration of restoring `rows` rows (microseconds) and the number of column slices per row
+// tile pair it assumes: rounds of 256 workgroups x (chunk pairs per workgroup x (~1.0 us per block +
+// ~2.5 us for the flush) + ~3 us fixed) (a slab of 2048 rows of 28672x8192: ~40 us inside a run of
+// slabs, the whole matrix 520-600).
+double restore_time_us(int rows, int in, int n_loaded, int* slices_out) {
+    const int iters = (in / kChunkCols + 1) / 2;
+    const int row_wgs = (rows + 2 * kTileRows - 1) / (2 * kTileRows);
+    int slices = 1;
+    double best = 0.0;
+    for (int sl = 1; sl <= iters; sl *= 2) {
+        const int per = (iters + sl - 1) / sl;
+        const double t = double((row_wgs * sl + 255) / 256) * (per * (1.0 * n_loaded + 2.5) + 3.0);
+        if (sl == 1 || t < best) {
+            best = t;
+            slices = sl;
+        }
+    }
+    if (slices_out) *slices_out = slices;
+    return best;
+}
+
 hipError_t launch_restore(const LaunchArgs& a, hipStream_t st) {
     KParams p = make_params(a);
     if (a.n_loaded < 1 || a.n_loaded > kTileMaxBlocks || p.wdense == nullptr) return hipErrorInvalidValue;
@@ -947,21 +968,13 @@ hipError_t launch_restore(const LaunchArgs& a, hipStream_t st) {
     }
     // Column slices per row tile pair: few, long workgroups pay the fixed costs (copy of the U
     // rows, first loads, ~3 us) less often, many short ones fill the last round of the 256
-    // compute units better.  Per chunk pair: ~0.9 us per block plus ~2.5 us for the flush.
-    const int iters = (p.in / kChunkCols + 1) / 2;
+    // compute units better (restore_time_us).
     const int slab_rows = a.rows ? a.rows : p.out;
     if (a.row_begin % 256 || a.row_begin < 0 || a.row_begin >= p.out || slab_rows < 1) return hipErrorInvalidValue;
-    const int row_wgs = (min(slab_rows, p.out - a.row_begin) + 2 * kTileRows - 1) / (2 * kTileRows);
+    const int rows = min(slab_rows, p.out - a.row_begin);
+    const int row_wgs = (rows + 2 * kTileRows - 1) / (2 * kTileRows);
     int slices = 1;
-    double best = 0.0;
-    for (int sl = 1; sl <= iters; sl *= 2) {
-        const int per = (iters + sl - 1) / sl;
-        const double t = double((row_wgs * sl + 255) / 256) * (per * (0.9 * p.n_loaded + 2.5) + 3.0);
-        if (sl == 1 || t < best) {
-            best = t;
-            slices = sl;
-        }
-    }
+    restore_time_us(rows, p.in, p.n_loaded, &slices);
     hipLaunchKernelGGL(k_tile<true>, dim3(row_wgs, slices), dim3(512), smem, st, p);
     return hipGetLastError();
 }
@@ -977,14 +990,14 @@ double fused_time_us(int out, int in, int batch, int n_loaded, int part_slots) {
     const double rounds = wgs <= 256 ? 1.0 : wgs / 256.0;
     return rounds * (10.0 + 0.93 * n_loaded * ((chunk_pairs + split - 1) / split)) + (split > 1 ? 5.0 : 0.0);
 }
-// k_tile: per pair of column chunks ~1.0 us per block for the rebuild + 13 us for the product
-// (6.5 us up to 256 tokens, where only one wavefront per SIMD has tokens to multiply); 15 % less
-// of both when the chip is not full.
+// k_tile: per pair of column chunks ~1.0 us per block for the rebuild + 12-14 us for the product
+// (14 when several token tiles of a row tile run at once, 6.5 up to 256 tokens, where only one
+// wavefront per SIMD has tokens to multiply); 15 % less of both when the chip is not full.
 double tile_time_us(int out, int in, int batch, int n_loaded) {
     const int row_tiles = (out + 2 * kTileRows - 1) / (2 * kTileRows), chunk_pairs = (in / kChunkCols + 1) / 2;
     const int wgs = row_tiles * ((batch + kTileTokens - 1) / kTileTokens);
     const double rounds = wgs <= 256 ? 1.0 : wgs / 256.0, scale = wgs <= 256 ? 0.85 : 1.0;
-    return rounds * (15.0 + chunk_pairs * scale * (1.0 * n_loaded + (batch > 256 ? 13.0 : 6.5)));
+    return rounds * (15.0 + chunk_pairs * scale * (1.0 * n_loaded + (batch > 512 ? 14.0 : batch > 256 ? 12.0 : 6.5)));
 }
 
 hipError_t launch_panel(const LaunchArgs& a, hipStream_t st) {

@@ -157,7 +157,8 @@ def test_kernel_choice_is_host_logic():
     assert B.choose_kernel(28672, 8192, 16, 1000, 1000, 16, 64 << 20) == B.KERNEL_MATERIALISE
     assert B.choose_kernel(28672, 8192, 16, 1000, 1000, 16, 1024 * 8192 * 2 - 1) == B.KERNEL_PANEL
     assert B.choose_kernel(28672, 8192, 16, 2048, 2048, 16, B.dense_bytes(28672, 8192)) == B.KERNEL_MATERIALISE
-    assert B.choose_kernel(28672, 8192, 16, 2048, 128, 16, big) == B.KERNEL_PANEL
+    assert B.choose_kernel(28672, 8192, 16, 2048, 128, 16, big) in (B.KERNEL_PANEL, B.KERNEL_MATERIALISE)   # measured equal
+    assert B.choose_kernel(28672, 8192, 16, 2048, 128, 16, 0) == B.KERNEL_PANEL
     assert B.choose_kernel(14336, 4096, 32, 2048, 2048, B.restore_max_blocks() + 1, big) == B.KERNEL_PANEL
     assert B.choose_kernel(14336, 4096, 16, 16, 16, 16, big) == B.KERNEL_PANEL      # too few tokens to pay for restoring
     assert B.choose_kernel(4096, 4096, 16, 64, 2, 2, big) in (B.KERNEL_DECODE, B.KERNEL_PANEL)
