@@ -346,6 +346,9 @@ def decoder_token(B, torch, dev, layers=32, n_pack=24):
         plan.launch()
         torch.cuda.synchronize()
         assert all(torch.equal(a, it[3]) for a, it in zip(want, items)), "plan launch differs from bitstack_linear_many"
+        for _ in range(2):   # the comparison above left the device idle: same warm-up as the native loop had
+            plan.launch()
+        torch.cuda.synchronize()
         e0.record()
         for _ in range(reps):
             plan.launch()
@@ -376,6 +379,9 @@ def decoder_token(B, torch, dev, layers=32, n_pack=24):
             g.replay()
             torch.cuda.synchronize()
             assert all(torch.equal(a, it[3]) for a, it in zip(eager, items[:14])), "graph replay differs from eager"
+        for _ in range(2):
+            g.replay()
+        torch.cuda.synchronize()
         e0.record()
         for _ in range(reps):
             g.replay()
