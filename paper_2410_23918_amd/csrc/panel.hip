@@ -339,43 +339,60 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
             }
     };
 
-    // ---- per-step inputs
+    // ---- per-step inputs: signs and V of one (chunk, block) step, both through one buffer descriptor
+    // over the loaded blocks (less than 4 GiB, checked by the launcher): the address of a load is a
+    // per-lane constant plus a scalar offset that moves by one block stride per step, so no vector
+    // instruction and only a handful of scalar ones go into addresses.
     struct Pos {
-        int it, i;   // team iteration (chunk), block
+        int i, ch;              // block, chunk (past the last step the last chunk is read again, harmlessly)
+        unsigned off_s, off_v;  // scalar offsets of the step's sign units and V panel
+    };
+    const unsigned stride32 = unsigned(p.block_stride), off_v32 = unsigned(p.off_v);
+    auto pos_at = [&](int it, int i) -> Pos {
+        Pos q;
+        q.i = i;
+        q.ch = min(c_lo + 2 * it + team, nch - 1);
+        q.off_s = unsigned(i) * stride32 + unsigned(q.ch) * kUnitBytes;
+        q.off_v = unsigned(i) * stride32 + off_v32 + unsigned(q.ch) * 8192u;
+        return q;
     };
     auto advance = [&](Pos q) -> Pos {
         if (++q.i == n) {
             q.i = 0;
-            ++q.it;
+            q.ch = min(q.ch + 2, nch - 1);
+            q.off_s = unsigned(q.ch) * kUnitBytes;
+            q.off_v = off_v32 + unsigned(q.ch) * 8192u;
+        } else {
+            q.off_s += stride32;
+            q.off_v += stride32;
         }
         return q;
     };
-    // past the last step the last chunk is read again, harmlessly
-    auto chunk_of = [&](Pos q) -> int { return min(c_lo + 2 * q.it + team, nch - 1); };
-    auto block_of = [&](Pos q) -> const unsigned char* { return p.blocks + size_t(q.i) * p.block_stride; };
+    __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(p.blocks), 0,
+                                                                   unsigned(n) * stride32, 0x00020000);
+    typedef int v4i_ __attribute__((ext_vector_type(4)));
+    typedef int v2i_ __attribute__((ext_vector_type(2)));
     // V: my wavefront needs, of every row (t, g, r) with g = my column half, the 8 columns
     // e = 8*(cw&1) .. +7, i.e. 16 of its 32 bytes; lane L takes rows (t = L/8, r = 2*(L%8) and + 1)
     struct VIn {
-        uint4 a, b;
+        v4i_ a, b;
     };
     const unsigned voff = unsigned((((lane >> 3) * 2 + (cw >> 1)) * 16 + 2 * (lane & 7)) * 32 + (cw & 1) * 16);
     auto fetch_v = [&](Pos q) -> VIn {
-        const unsigned char* src = block_of(q) + p.off_v + size_t(chunk_of(q)) * 8192;
         VIn v;
-        v.a = *reinterpret_cast<const uint4*>(src + voff);
-        v.b = *reinterpret_cast<const uint4*>(src + voff + 32);
+        v.a = __builtin_amdgcn_raw_buffer_load_b128(brs, voff, q.off_v, 0);
+        v.b = __builtin_amdgcn_raw_buffer_load_b128(brs, voff + 32, q.off_v, 0);
         return v;
     };
     struct SIn {
-        uint2 w[2];   // per row group: my row's two sign words of my 64 columns
+        v2i_ w[2];   // per row group: my row's two sign words of my 64 columns
     };
     const unsigned soff[2] = {unsigned((size_t(rtc[0]) * nch_all) * kUnitBytes + ((cw >> 1) * 32 + ln) * 16 + (cw & 1) * 8),
                               unsigned((size_t(rtc[1]) * nch_all) * kUnitBytes + ((cw >> 1) * 32 + ln) * 16 + (cw & 1) * 8)};
     auto fetch_s = [&](Pos q) -> SIn {
-        const unsigned char* src = block_of(q) + size_t(chunk_of(q)) * kUnitBytes;
         SIn v;
-        v.w[0] = *reinterpret_cast<const uint2*>(src + soff[0]);
-        v.w[1] = *reinterpret_cast<const uint2*>(src + soff[1]);
+        v.w[0] = __builtin_amdgcn_raw_buffer_load_b64(brs, soff[0], q.off_s, 0);
+        v.w[1] = __builtin_amdgcn_raw_buffer_load_b64(brs, soff[1], q.off_s, 0);
         return v;
     };
 
@@ -389,8 +406,8 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
         vsrc_off[tile] = (t * kVtStride + 8 * hl * 4) * 4 + e * 2;
     }
     auto stage_v = [&](VIn v, int buf) {
-        *reinterpret_cast<uint4*>(vdst + buf * kVPriv) = v.a;        // rank r
-        *reinterpret_cast<uint4*>(vdst + buf * kVPriv + 16) = v.b;   // rank r + 1
+        *reinterpret_cast<v4i_*>(vdst + buf * kVPriv) = v.a;        // rank r
+        *reinterpret_cast<v4i_*>(vdst + buf * kVPriv + 16) = v.b;   // rank r + 1
     };
     auto read_vf = [&](int buf, int tile) -> v8h {
         // A operand of the magnitude product: my column's ranks 8*hl .. 8*hl + 7
@@ -410,49 +427,63 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) yacc[rg][v] = 0.0f;
 
+    // per-lane shifts that bring the sign bits of a register pair (word bits 8*mf + k + 4*hl and that + 16)
+    // to bits 15 and 31
+    unsigned sh[2][4];
+#pragma unroll
+    for (int mf = 0; mf < 2; ++mf)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) sh[mf][k] = unsigned(15 - 8 * mf - k - 4 * hl);
+
     auto compute = [&](const SIn& sg, v8h uf0, v8h uf1, v8h vf0, v8h vf1) {
+        // magnitude tile C[i = column][n = row]: lane (row ln), register v holds column 8*(v/4) + 4*hl + v%4
+        auto magnitude = [&](int tile, int rg) -> v16f {
+            v16f z;
 #pragma unroll
-        for (int tile = 0; tile < 2; ++tile) {
-            const v8h vf = tile ? vf1 : vf0;
+            for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+            return __builtin_amdgcn_mfma_f32_32x32x16_f16(tile ? vf1 : vf0, rg ? uf1 : uf0, z, 0, 0, 0);
+        };
+        auto apply = [&](const v16f& m, int tile, int rg) {
+            const unsigned wrd = unsigned(tile ? sg.w[rg].y : sg.w[rg].x);
 #pragma unroll
-            for (int rg = 0; rg < 2; ++rg) {
-                v16f z;
+            for (int mf = 0; mf < 2; ++mf) {
+                unsigned r4[4];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) z[v] = 0.0f;
-                // C[i = column][n = row]: lane (row ln), register v holds column 8*(v/4) + 4*hl + v%4
-                const v16f m = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, rg ? uf1 : uf0, z, 0, 0, 0);
-                // inverted, so that a set bit marks a negative sign; bit of register v at 8*(v/4) + v%4
-                const unsigned wrd = ~(tile ? sg.w[rg].y : sg.w[rg].x) >> (4 * hl);
-#pragma unroll
-                for (int mf = 0; mf < 2; ++mf) {
-                    unsigned r4[4];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-                        h2 c;
-                        c[0] = _Float16(m[4 * mf + k]);
-                        c[1] = _Float16(m[4 * mf + k + 8]);
-                        // sign bits of the pair: word bits 8*mf + k and 16 + 8*mf + k -> bits 15 and 31
-                        const unsigned flip = (wrd << (15 - 8 * mf - k)) & 0x80008000u;
-                        r4[k] = __builtin_bit_cast(unsigned, c) ^ flip;
-                    }
-                    yacc[rg] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[tile][mf], __builtin_bit_cast(v8h, r4), yacc[rg], 0, 0, 0);
+                for (int k = 0; k < 4; ++k) {
+                    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+                    h2 c;
+                    c[0] = _Float16(m[4 * mf + k]);
+                    c[1] = _Float16(m[4 * mf + k + 8]);
+                    // a cleared bit marks a negative sign
+                    const unsigned flip = ~(wrd << sh[mf][k]) & 0x80008000u;
+                    r4[k] = __builtin_bit_cast(unsigned, c) ^ flip;
                 }
+                yacc[rg] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[tile][mf], __builtin_bit_cast(v8h, r4), yacc[rg], 0, 0, 0);
             }
-        }
+        };
+        // the magnitude product of the next (tile, row group) is issued before the vector work on the
+        // current one, which then covers its latency
+        v16f m0 = magnitude(0, 0);
+        v16f m1 = magnitude(0, 1);
+        apply(m0, 0, 0);
+        m0 = magnitude(1, 0);
+        apply(m1, 0, 1);
+        m1 = magnitude(1, 1);
+        apply(m0, 1, 0);
+        apply(m1, 1, 1);
     };
 
     // ---- prologue: steps 0..2 on their way, chunk 0's activations and V(0) fragments ready
-    Pos q = {0, 0};
+    Pos q = pos_at(0, 0);
     VIn vA = fetch_v(q);
     SIn sA = fetch_s(q);
     q = advance(q);
     VIn vB = fetch_v(q);
     SIn sB = fetch_s(q);
-    q = advance(q);          // q: position of step s + 2 (signs)
-    Pos qv = advance(q);     // qv: position of step s + 3 (V)
+    q = advance(q);
     VIn vC = fetch_v(q);
-    SIn sC;
+    SIn sC = fetch_s(q);
+    q = advance(q);          // q: position of step s + 3
     store_x(fetch_x(0), 0);
     stage_v(vA, 0);
     v8h vf0 = read_vf(0, 0), vf1 = read_vf(0, 1);
@@ -461,8 +492,8 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
     __syncthreads();         // U cache complete
 
     int ci = 0, it = 0;      // block index inside the chunk, team iteration
-    // one step; CUR: set in use, NXT: set whose V goes to LDS now, FAR: set that receives signs(s+2);
-    // V(s+3) lands in CUR's V registers (V(s) left them one step ago)
+    // one step; CUR: set in use, NXT: set whose V goes to LDS now.  V(s+3) lands in CUR's V registers
+    // (V(s) left them one step ago), signs(s+3) in CUR's sign registers once the step has used them
 #define BS_FUSED_STEP(S, CUR, NXT, FAR)                                                    \
     {                                                                                      \
         const v8h uf0 = read_u(ci, 0), uf1 = read_u(ci, 1);                                \
@@ -473,11 +504,10 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
             build_afr();                                                                   \
             xn = fetch_x(it + 1);                                                          \
         }                                                                                  \
-        s##FAR = fetch_s(q);                                                               \
-        v##CUR = fetch_v(qv);                                                              \
-        q = advance(q);                                                                    \
-        qv = advance(qv);                                                                  \
+        v##CUR = fetch_v(q);                                                               \
         compute(s##CUR, uf0, uf1, vf0, vf1);                                               \
+        s##CUR = fetch_s(q);                                                               \
+        q = advance(q);                                                                    \
         vf0 = vn0;                                                                         \
         vf1 = vn1;                                                                         \
         if (++ci == n) {                                                                   \
@@ -562,7 +592,9 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
     }
 }
 
-static bool fused_fits(const KParams& p) { return p.n_loaded <= kFusedMaxBlocks; }
+static bool fused_fits(const KParams& p) {   // U cache in LDS; one 32-bit buffer descriptor over the loaded blocks
+    return p.n_loaded <= kFusedMaxBlocks && size_t(p.n_loaded) * p.block_stride < (size_t(1) << 32);
+}
 
 constexpr int kFusedMaxSplit = 8;
 
