@@ -698,39 +698,56 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
             p.blocks + size_t(i) * p.block_stride + p.off_u + size_t(row) * 32 + (piece & 1) * 16);
     }
 
+    // per-step inputs through one buffer descriptor over the loaded blocks, as in k_fused: per-lane
+    // constant plus a scalar offset that moves by one block stride per step
     struct Pos {
-        int it, i;
+        int i, ch;
+        unsigned off_s, off_v;
+    };
+    const unsigned stride32 = unsigned(p.block_stride), off_v32 = unsigned(p.off_v);
+    auto pos_at = [&](int it, int i) -> Pos {
+        Pos q;
+        q.i = i;
+        q.ch = min(2 * it + team, nch - 1);
+        q.off_s = unsigned(i) * stride32 + unsigned(q.ch) * kUnitBytes;
+        q.off_v = unsigned(i) * stride32 + off_v32 + unsigned(q.ch) * 8192u;
+        return q;
     };
     auto advance = [&](Pos q) -> Pos {
         if (++q.i == n) {
             q.i = 0;
-            ++q.it;
+            q.ch = min(q.ch + 2, nch - 1);
+            q.off_s = unsigned(q.ch) * kUnitBytes;
+            q.off_v = off_v32 + unsigned(q.ch) * 8192u;
+        } else {
+            q.off_s += stride32;
+            q.off_v += stride32;
         }
         return q;
     };
-    auto chunk_of = [&](Pos q) -> int { return min(2 * q.it + team, nch - 1); };
-    auto block_of = [&](Pos q) -> const unsigned char* { return p.blocks + size_t(q.i) * p.block_stride; };
+    __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(p.blocks), 0,
+                                                                   unsigned(n) * stride32, 0x00020000);
+    typedef int v4i_ __attribute__((ext_vector_type(4)));
+    typedef int v2i_ __attribute__((ext_vector_type(2)));
     struct VIn {
-        uint4 a, b;
+        v4i_ a, b;
     };
     const unsigned voff = unsigned((((lane >> 3) * 2 + (cw >> 1)) * 16 + 2 * (lane & 7)) * 32 + (cw & 1) * 16);
     auto fetch_v = [&](Pos q) -> VIn {
-        const unsigned char* src = block_of(q) + p.off_v + size_t(chunk_of(q)) * 8192;
         VIn v;
-        v.a = *reinterpret_cast<const uint4*>(src + voff);
-        v.b = *reinterpret_cast<const uint4*>(src + voff + 32);
+        v.a = __builtin_amdgcn_raw_buffer_load_b128(brs, voff, q.off_v, 0);
+        v.b = __builtin_amdgcn_raw_buffer_load_b128(brs, voff + 32, q.off_v, 0);
         return v;
     };
     struct SIn {
-        uint2 w[2];
+        v2i_ w[2];
     };
     const unsigned soff[2] = {unsigned((size_t(rtc[0]) * nch) * kUnitBytes + ((cw >> 1) * 32 + ln) * 16 + (cw & 1) * 8),
                               unsigned((size_t(rtc[1]) * nch) * kUnitBytes + ((cw >> 1) * 32 + ln) * 16 + (cw & 1) * 8)};
     auto fetch_s = [&](Pos q) -> SIn {
-        const unsigned char* src = block_of(q) + size_t(chunk_of(q)) * kUnitBytes;
         SIn v;
-        v.w[0] = *reinterpret_cast<const uint2*>(src + soff[0]);
-        v.w[1] = *reinterpret_cast<const uint2*>(src + soff[1]);
+        v.w[0] = __builtin_amdgcn_raw_buffer_load_b64(brs, soff[0], q.off_s, 0);
+        v.w[1] = __builtin_amdgcn_raw_buffer_load_b64(brs, soff[1], q.off_s, 0);
         return v;
     };
     unsigned char* const vdst = vpriv + ((lane >> 3) * kVtStride + 2 * (lane & 7) * 4) * 4;
@@ -741,8 +758,8 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
         vsrc_off[tile] = (t * kVtStride + 8 * hl * 4) * 4 + e * 2;
     }
     auto stage_v = [&](VIn v, int buf) {
-        *reinterpret_cast<uint4*>(vdst + buf * kVPriv) = v.a;
-        *reinterpret_cast<uint4*>(vdst + buf * kVPriv + 16) = v.b;
+        *reinterpret_cast<v4i_*>(vdst + buf * kVPriv) = v.a;
+        *reinterpret_cast<v4i_*>(vdst + buf * kVPriv + 16) = v.b;
     };
     auto read_vf = [&](int buf, int tile) -> v8h {
         v8h vf;
@@ -774,6 +791,16 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) yacc[a][b][v] = 0.0f;
 
+    // shifts that bring the sign bits of a register pair (word bits 8*mf + k + 4*hl and that + 16) to
+    // bits 15 and 31: per lane (eight registers) where registers are to spare, else the word is moved
+    // down by 4*hl first and the shifts are immediates
+    constexpr bool kLaneShift = kRestore;
+    unsigned sh[2][4];
+#pragma unroll
+    for (int mf = 0; mf < 2; ++mf)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) sh[mf][k] = unsigned(15 - 8 * mf - k) - (kLaneShift ? unsigned(4 * hl) : 0u);
+
     // first = the chunk's first block: the accumulator starts from zero instead of being cleared
     // beforehand, so that its 64 registers are free during the product stage
     auto magnitude = [&](int tb, v8h uf0, v8h uf1, v8h vf0, v8h vf1) -> v16f {
@@ -784,7 +811,7 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
     };
     auto sign_and_add = [&](auto first, int tb, const v16f& m, const SIn& sg) {
         const int tile = tb >> 1, rg = tb & 1;
-        const unsigned wrd = ~(tile ? sg.w[rg].y : sg.w[rg].x) >> (4 * hl);
+        const unsigned wrd = unsigned(tile ? sg.w[rg].y : sg.w[rg].x) >> (kLaneShift ? 0 : 4 * hl);
 #pragma unroll
         for (int mf = 0; mf < 2; ++mf) {
             unsigned r4[4];
@@ -794,7 +821,7 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
                 h2 c;
                 c[0] = _Float16(m[4 * mf + k]);
                 c[1] = _Float16(m[4 * mf + k + 8]);
-                const unsigned flip = (wrd << (15 - 8 * mf - k)) & 0x80008000u;
+                const unsigned flip = ~(wrd << sh[mf][k]) & 0x80008000u;   // a cleared bit marks a negative sign
                 r4[k] = __builtin_bit_cast(unsigned, c) ^ flip;
             }
             if (decltype(first)::value && mf == 0) {
@@ -810,8 +837,21 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
     };
     // tile-blocks tb = 2 * tile + row group
     auto rebuild = [&](auto first, const SIn& sg, v8h uf0, v8h uf1, v8h vf0, v8h vf1) {
+        if (kRestore) {
+            // registers to spare: the magnitude product of the next tile-block is issued before the
+            // vector work on the current one, which then covers its latency
+            v16f m0 = magnitude(0, uf0, uf1, vf0, vf1);
+            v16f m1 = magnitude(1, uf0, uf1, vf0, vf1);
+            sign_and_add(first, 0, m0, sg);
+            m0 = magnitude(2, uf0, uf1, vf0, vf1);
+            sign_and_add(first, 1, m1, sg);
+            m1 = magnitude(3, uf0, uf1, vf0, vf1);
+            sign_and_add(first, 2, m0, sg);
+            sign_and_add(first, 3, m1, sg);
+        } else {
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb) sign_and_add(first, tb, magnitude(tb, uf0, uf1, vf0, vf1), sg);
+            for (int tb = 0; tb < 4; ++tb) sign_and_add(first, tb, magnitude(tb, uf0, uf1, vf0, vf1), sg);
+        }
     };
 
     // end of a chunk: park my piece of W' diag(1/s) in LDS, then the product stage for both teams' chunks
@@ -888,16 +928,22 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
         lds_barrier();   // tiles free for the next pair of chunks
     };
 
-    Pos q = {it_first, 0};
+    Pos q = pos_at(it_first, 0);
     VIn vA = fetch_v(q);
     SIn sA = fetch_s(q);
     q = advance(q);
     VIn vB = fetch_v(q);
     SIn sB = fetch_s(q);
     q = advance(q);
-    Pos qv = advance(q);
     VIn vC = fetch_v(q);
+    // Signs of step s + 3 are requested once step s has used its own (into the same registers) where
+    // registers are to spare; else signs run one step behind V (step s + 2 at the start of step s, into
+    // the third set) and need a position of their own.
+    constexpr bool kSignsLate = kRestore;
+    Pos qs = q;       // position of step s + 2
     SIn sC;
+    if (kSignsLate) sC = fetch_s(q);
+    q = advance(q);   // position of step s + 3
     stage_v(vA, 0);
     v8h vf0 = read_vf(0, 0), vf1 = read_vf(0, 1);
     __syncthreads();   // U cache complete
@@ -908,14 +954,17 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
         const v8h uf0 = read_u(ci, 0), uf1 = read_u(ci, 1);                                \
         stage_v(v##NXT, ((S) + 1) & 1);                                                    \
         const v8h vn0 = read_vf(((S) + 1) & 1, 0), vn1 = read_vf(((S) + 1) & 1, 1);        \
-        s##FAR = fetch_s(q);                                                               \
-        v##CUR = fetch_v(qv);                                                              \
-        q = advance(q);                                                                    \
-        qv = advance(qv);                                                                  \
+        if (!kSignsLate) {                                                                 \
+            s##FAR = fetch_s(qs);                                                          \
+            qs = advance(qs);                                                              \
+        }                                                                                  \
+        v##CUR = fetch_v(q);                                                               \
         if (ci == 0)                                                                       \
             rebuild(std::true_type{}, s##CUR, uf0, uf1, vf0, vf1);                         \
         else                                                                               \
             rebuild(std::false_type{}, s##CUR, uf0, uf1, vf0, vf1);                        \
+        if (kSignsLate) s##CUR = fetch_s(q);                                               \
+        q = advance(q);                                                                    \
         vf0 = vn0;                                                                         \
         vf1 = vn1;                                                                         \
         if (++ci == n) {                                                                   \
@@ -946,7 +995,9 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
             }
 }
 
-static bool tile_fits(const KParams& p) { return p.n_loaded <= kTileMaxBlocks && p.xpack != nullptr; }
+static bool tile_fits(const KParams& p) {   // U cache in LDS; one 32-bit buffer descriptor over the loaded blocks
+    return p.n_loaded <= kTileMaxBlocks && p.xpack != nullptr && size_t(p.n_loaded) * p.block_stride < (size_t(1) << 32);
+}
 
 static hipError_t launch_tile(const KParams& p, hipStream_t st) {
     const size_t smem = size_t(kTileFixedLds) + size_t(p.n_loaded) * 2048;
