@@ -306,7 +306,8 @@ int bitstack_linear_select(const void* x, int batch, const bitstack_weight_t* bl
  * as fp16, row-major [out][in], summed in fp32 over the blocks and rounded once.
  *   w_dense: device, caller-owned, 256-byte aligned, w_dense_bytes >= bitstack_dense_bytes(out, in)
  *   (BITSTACK_E_BUFSIZE otherwise).  n_loaded in [0, min(resident blocks,
- *   bitstack_restore_max_blocks())], 0 gives a zero matrix; BITSTACK_E_RANGE otherwise.
+ *   bitstack_restore_max_blocks())], 0 gives a zero matrix; BITSTACK_E_RANGE otherwise, also when the
+ *   loaded blocks take 4 GiB or more (the kernel reaches them through 32-bit offsets).
  * bitstack_linear_dense computes y = x w_dense^T for x device fp16 [batch][in], y device
  *   [batch][out] of y_dtype; `blocks` supplies the shape; 1 <= batch <= max_batch given at pack
  *   time (BITSTACK_E_RANGE otherwise); x and w_dense below 4 GiB each.

@@ -339,7 +339,7 @@ static int choose_kernel(const Geometry& g, int batch, int n_loaded, size_t work
     const int slab = slab_rows(g, workspace_bytes);
     // (the dense product addresses x and a slab of the dense weight with 32-bit byte offsets)
     const bool dense_ok = size_t(batch) * g.in * 2 <= 0xffffffffull && size_t(slab) * g.in * 2 <= 0xffffffffull;
-    if (n_loaded <= restore_max_blocks() && slab > 0 && dense_ok) {
+    if (restore_fits(g.block_stride, n_loaded) && slab > 0 && dense_ok) {
         // per slab of rows: restore + product, two launches (~4 us each between kernels of one stream)
         double t_mat = 0.0;
         for (int r0 = 0; r0 < g.out; r0 += slab) {
@@ -470,7 +470,7 @@ int bitstack_restore_weight(const bitstack_weight_t* w, int n_loaded, void* w_de
                             bitstack_stream_t stream) {
     int rc = dense_args(w, w_dense, w_dense_bytes, true);
     if (rc) return rc;
-    if (n_loaded < 0 || n_loaded > w->resident || n_loaded > restore_max_blocks()) return BITSTACK_E_RANGE;
+    if (n_loaded < 0 || n_loaded > w->resident || !restore_fits(w->geo.block_stride, n_loaded)) return BITSTACK_E_RANGE;
     LaunchArgs a;
     a.x = nullptr;
     a.y = nullptr;
@@ -519,7 +519,7 @@ int bitstack_linear_materialised(const void* x, int batch, const bitstack_weight
     const Geometry& g = w->geo;
     const int slab = slab_rows(g, w_dense_bytes);
     if (slab == 0) return BITSTACK_E_BUFSIZE;
-    if (n_loaded < 0 || n_loaded > w->resident || n_loaded > restore_max_blocks()) return BITSTACK_E_RANGE;
+    if (n_loaded < 0 || n_loaded > w->resident || !restore_fits(w->geo.block_stride, n_loaded)) return BITSTACK_E_RANGE;
     if (batch < 1 || batch > g.max_batch) return BITSTACK_E_RANGE;
     if (y_dtype != BITSTACK_Y_F16 && y_dtype != BITSTACK_Y_F32) return BITSTACK_E_ARG;
     if (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16) return BITSTACK_E_ALIGN;

@@ -70,6 +70,8 @@ double restore_time_us(int rows, int in, int n_loaded, int* slices_out);   // an
 double fused_time_us(int out, int in, int batch, int n_loaded, int part_slots);
 double tile_time_us(int out, int in, int batch, int n_loaded);
 int restore_max_blocks();
+// can the restore kernel take n_loaded blocks of this stride? (block count, and their bytes below 4 GiB)
+bool restore_fits(size_t block_stride, int n_loaded);
 // decomposition on the device (decompose.hip): W fp32 [out][in], s fp32 [in] (device copy inside the
 // workspace), outputs canonical sign words and fp16 factors on the device
 size_t decompose_workspace_bytes(int out, int in, int slices);

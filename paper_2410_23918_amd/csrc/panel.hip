@@ -1039,7 +1039,7 @@ double restore_time_us(int rows, int in, int n_loaded, int* slices_out) {
 
 hipError_t launch_restore(const LaunchArgs& a, hipStream_t st) {
     KParams p = make_params(a);
-    if (a.n_loaded < 1 || a.n_loaded > kTileMaxBlocks || p.wdense == nullptr) return hipErrorInvalidValue;
+    if (a.n_loaded < 1 || !restore_fits(p.block_stride, a.n_loaded) || p.wdense == nullptr) return hipErrorInvalidValue;
     const size_t smem = size_t(kTileFixedLds) + size_t(p.n_loaded) * 2048;
     static std::atomic<bool> attr_set{false};   // setting the attribute twice is harmless
     if (!attr_set) {
@@ -1062,6 +1062,10 @@ hipError_t launch_restore(const LaunchArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 int restore_max_blocks() { return kTileMaxBlocks; }
+// U cache in LDS; the kernel reaches the loaded blocks through one buffer descriptor with 32-bit offsets
+bool restore_fits(size_t block_stride, int n_loaded) {
+    return n_loaded <= kTileMaxBlocks && size_t(n_loaded) * block_stride < (size_t(1) << 32);
+}
 
 // Estimated durations (microseconds, constants fitted to measurements).  k_fused: per round of
 // 256 workgroups ~10 us fixed + ~0.93 us per block and pair of column chunks of a workgroup; later

@@ -177,6 +177,11 @@ def test_kernel_choice_is_host_logic():
     # the dense product addresses x with 32-bit byte offsets: a batch beyond that stays with the weight-tile kernel
     assert B.choose_kernel(4096, 8192, 4, 3000, 3000, 4, 0) == B.KERNEL_MATERIALISE
     assert B.choose_kernel(4096, 8192, 4, 300000, 300000, 4, 0) == B.KERNEL_PANEL
+    # the restore kernel reaches the loaded blocks through 32-bit offsets: 28 blocks of 36864 x 32768 stay
+    # below 4 GiB, 29 do not
+    assert 28 * B.block_bytes(36864, 32768) < 2 ** 32 <= 29 * B.block_bytes(36864, 32768)
+    assert B.choose_kernel(36864, 32768, 29, 2048, 2048, 28, big) == B.KERNEL_MATERIALISE
+    assert B.choose_kernel(36864, 32768, 29, 2048, 2048, 29, big) == B.KERNEL_PANEL
     L = B.lib()
     assert L.bitstack_choose_kernel(4096, 100, 16, 1, 1, 1, 0) == -2
     assert L.bitstack_choose_kernel(4096, 4096, 16, 8, 9, 1, 0) == -3
