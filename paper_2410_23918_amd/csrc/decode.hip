@@ -736,14 +736,13 @@ bool plan_decode(const LaunchArgs* a, int count, DecodePlan* best) {
             const int npc = (ksc + kPieceChunks - 1) / kPieceChunks;
             DecodePlan pl;
             pl.tiles = R;
-            long work = 0, pairs_all = 0;
+            long work = 0;
             int tallest = 1;
             for (int i = 0; i < count; ++i) {
                 pl.m[i].n_rs = (a[i].geo.out + R * 256 - 1) / (R * 256);
                 pl.m[i].n_ks = n_ks;
                 pl.m[i].ks_chunks = ksc;
                 const long pairs = long(pl.m[i].n_rs) * n_ks;
-                pairs_all += pairs;
                 work += pairs * a[i].n_loaded;
                 tallest = tallest > a[i].n_loaded ? tallest : a[i].n_loaded;
             }

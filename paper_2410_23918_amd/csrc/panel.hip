@@ -41,7 +41,6 @@ constexpr int kPanelLd = 264;         // fp16 elements per LDS row of a 256-colu
 constexpr int kFusedMaxBatch = kSmallBatch;   // above this the weight-tile kernels are used
 constexpr int kVRow = 48;
 constexpr int kVPos = 16 * kVRow + 16;
-constexpr int kVBuf = 16 * kVPos;
 
 // TT token tiles of 128 tokens per workgroup: the weight tile is rebuilt once per column chunk
 // and reused for all of them (accumulators: 32 registers per tile and lane).
