@@ -395,26 +395,31 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
         return v;
     };
 
-    // my private V piece: dword address of (t, r, column pair c2) = t * kVtStride + r * 4 + c2; the
-    // stride of 68 spreads both the 128-bit row writes and the 16-bit fragment gathers over all banks
-    unsigned char* const vdst = vpriv + ((lane >> 3) * kVtStride + 2 * (lane & 7) * 4) * 4;
+    // my private V piece, transposed on the way in: dword address of (t, column e, rank pair) =
+    // t * kVtStride + e * 8 + pair.  A lane arrives with ranks 2j and 2j + 1 of eight columns (two
+    // columns per register) and scatters them as sixteen 16-bit writes; a fragment "one column, 8 ranks"
+    // is then one 128-bit read (the stride of 68 keeps the writes to two lanes per bank).
+    unsigned short* const vdst = reinterpret_cast<unsigned short*>(vpriv) + ((lane >> 3) * kVtStride + (lane & 7)) * 2;
     int vsrc_off[2];
 #pragma unroll
     for (int tile = 0; tile < 2; ++tile) {
         const int b = ln >> 3, t = ln & 7, e = tile * 4 + b;   // e: column of my 8 within a row
-        vsrc_off[tile] = (t * kVtStride + 8 * hl * 4) * 4 + e * 2;
+        vsrc_off[tile] = (t * kVtStride + e * 8 + 4 * hl) * 4;
     }
     auto stage_v = [&](VIn v, int buf) {
-        *reinterpret_cast<v4i_*>(vdst + buf * kVPriv) = v.a;        // rank r
-        *reinterpret_cast<v4i_*>(vdst + buf * kVPriv + 16) = v.b;   // rank r + 1
+        unsigned short* const d = vdst + buf * (kVPriv / 2);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const unsigned a = unsigned(v.a[i]), b = unsigned(v.b[i]);   // rank 2j / 2j + 1, columns 2i (low half) and 2i + 1
+            d[(2 * i) * 16] = static_cast<unsigned short>(a);
+            d[(2 * i) * 16 + 1] = static_cast<unsigned short>(b);
+            d[(2 * i + 1) * 16] = static_cast<unsigned short>(a >> 16);
+            d[(2 * i + 1) * 16 + 1] = static_cast<unsigned short>(b >> 16);
+        }
     };
     auto read_vf = [&](int buf, int tile) -> v8h {
         // A operand of the magnitude product: my column's ranks 8*hl .. 8*hl + 7
-        v8h vf;
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-            vf[k] = *reinterpret_cast<const _Float16*>(vpriv + buf * kVPriv + vsrc_off[tile] + k * 16);
-        return vf;
+        return *reinterpret_cast<const v8h*>(vpriv + buf * kVPriv + vsrc_off[tile]);
     };
     auto read_u = [&](int i, int rg) -> v8h {   // my row's U, ranks 8*hl .. 8*hl + 7
         return *reinterpret_cast<const v8h*>(ucache + ((i * 64 + rg * 32 + ln) * 2 + hl) * 16);
@@ -749,23 +754,28 @@ __global__ __launch_bounds__(512) void k_tile(KParams p) {
         v.w[1] = __builtin_amdgcn_raw_buffer_load_b64(brs, soff[1], q.off_s, 0);
         return v;
     };
-    unsigned char* const vdst = vpriv + ((lane >> 3) * kVtStride + 2 * (lane & 7) * 4) * 4;
+    // private V piece transposed on the way in, as in k_fused: (t, column e, rank pair) at dword
+    // t * kVtStride + e * 8 + pair; sixteen 16-bit writes per lane, one 128-bit read per fragment
+    unsigned short* const vdst = reinterpret_cast<unsigned short*>(vpriv) + ((lane >> 3) * kVtStride + (lane & 7)) * 2;
     int vsrc_off[2];
 #pragma unroll
     for (int tile = 0; tile < 2; ++tile) {
         const int b = ln >> 3, t = ln & 7, e = tile * 4 + b;
-        vsrc_off[tile] = (t * kVtStride + 8 * hl * 4) * 4 + e * 2;
+        vsrc_off[tile] = (t * kVtStride + e * 8 + 4 * hl) * 4;
     }
     auto stage_v = [&](VIn v, int buf) {
-        *reinterpret_cast<v4i_*>(vdst + buf * kVPriv) = v.a;
-        *reinterpret_cast<v4i_*>(vdst + buf * kVPriv + 16) = v.b;
+        unsigned short* const d = vdst + buf * (kVPriv / 2);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const unsigned a = unsigned(v.a[i]), b = unsigned(v.b[i]);
+            d[(2 * i) * 16] = static_cast<unsigned short>(a);
+            d[(2 * i) * 16 + 1] = static_cast<unsigned short>(b);
+            d[(2 * i + 1) * 16] = static_cast<unsigned short>(a >> 16);
+            d[(2 * i + 1) * 16 + 1] = static_cast<unsigned short>(b >> 16);
+        }
     };
     auto read_vf = [&](int buf, int tile) -> v8h {
-        v8h vf;
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-            vf[k] = *reinterpret_cast<const _Float16*>(vpriv + buf * kVPriv + vsrc_off[tile] + k * 16);
-        return vf;
+        return *reinterpret_cast<const v8h*>(vpriv + buf * kVPriv + vsrc_off[tile]);
     };
     auto read_u = [&](int i, int rg) -> v8h {
         return *reinterpret_cast<const v8h*>(ucache + ((i * 64 + rg * 32 + ln) * 2 + hl) * 16);
