@@ -1026,7 +1026,7 @@ static hipError_t launch_tile(const KParams& p, hipStream_t st) {
 
 // W' diag(1/s) of the loaded prefix as a dense fp16 matrix [out][in] (row-major) at a.wdense.
 // Estimated duration of restoring `rows` rows (microseconds) and the number of column slices per row
-// tile pair it assumes: rounds of 256 workgroups x (chunk pairs per workgroup x (~1.0 us per block +
+// tile pair it assumes: rounds of 256 workgroups x (chunk pairs per workgroup x (~0.93 us per block +
 // ~2.5 us for the flush) + ~3 us fixed) (a slab of 2048 rows of 28672x8192: ~40 us inside a run of
 // slabs, the whole matrix 520-600).
 double restore_time_us(int rows, int in, int n_loaded, int* slices_out) {
@@ -1036,7 +1036,7 @@ double restore_time_us(int rows, int in, int n_loaded, int* slices_out) {
     double best = 0.0;
     for (int sl = 1; sl <= iters; sl *= 2) {
         const int per = (iters + sl - 1) / sl;
-        const double t = double((row_wgs * sl + 255) / 256) * (per * (1.0 * n_loaded + 2.5) + 3.0);
+        const double t = double((row_wgs * sl + 255) / 256) * (per * (0.93 * n_loaded + 2.5) + 3.0);
         if (sl == 1 || t < best) {
             best = t;
             slices = sl;
@@ -1077,23 +1077,23 @@ bool restore_fits(size_t block_stride, int n_loaded) {
 }
 
 // Estimated durations (microseconds, constants fitted to measurements).  k_fused: per round of
-// 256 workgroups ~10 us fixed + ~0.93 us per block and pair of column chunks of a workgroup; later
+// 256 workgroups ~8 us fixed + ~0.83 us per block and pair of column chunks of a workgroup; later
 // workgroups start as earlier ones end, so rounds beyond the first count fractionally.
 double fused_time_us(int out, int in, int batch, int n_loaded, int part_slots) {
     const int row_tiles = (out + 2 * kTileRows - 1) / (2 * kTileRows), chunk_pairs = (in / kChunkCols + 1) / 2;
     const int split = small_batch_split(out, in, batch, part_slots);
     const int wgs = row_tiles * ((batch + 31) / 32) * split;
     const double rounds = wgs <= 256 ? 1.0 : wgs / 256.0;
-    return rounds * (10.0 + 0.93 * n_loaded * ((chunk_pairs + split - 1) / split)) + (split > 1 ? 5.0 : 0.0);
+    return rounds * (8.0 + 0.83 * n_loaded * ((chunk_pairs + split - 1) / split)) + (split > 1 ? 4.0 : 0.0);
 }
-// k_tile: per pair of column chunks ~1.0 us per block for the rebuild + 12-14 us for the product
+// k_tile: per pair of column chunks ~0.9 us per block for the rebuild + 12-14 us for the product
 // (14 when several token tiles of a row tile run at once, 6.5 up to 256 tokens, where only one
 // wavefront per SIMD has tokens to multiply); 15 % less of both when the chip is not full.
 double tile_time_us(int out, int in, int batch, int n_loaded) {
     const int row_tiles = (out + 2 * kTileRows - 1) / (2 * kTileRows), chunk_pairs = (in / kChunkCols + 1) / 2;
     const int wgs = row_tiles * ((batch + kTileTokens - 1) / kTileTokens);
     const double rounds = wgs <= 256 ? 1.0 : wgs / 256.0, scale = wgs <= 256 ? 0.85 : 1.0;
-    return rounds * (15.0 + chunk_pairs * scale * (1.0 * n_loaded + (batch > 512 ? 14.0 : batch > 256 ? 12.0 : 6.5)));
+    return rounds * (15.0 + chunk_pairs * scale * (0.9 * n_loaded + (batch > 512 ? 14.0 : batch > 256 ? 12.0 : 6.5)));
 }
 
 hipError_t launch_panel(const LaunchArgs& a, hipStream_t st) {
