@@ -427,18 +427,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_decode(KGroup grp) {
             frag[(c * 8 + t) * 64 + lane_hi] = H;
             frag[(c * 8 + t) * 64 + lane_hi + 4] = L;
         }
-        // integer column sums of the quantised panel per rank and byte half: add up the lanes
-        // that hold the same ranks (lane bits 3..5), then one LDS atomic per rank, half and wavefront
+        // integer column sums of the quantised panel per rank and byte half: the lanes that hold the
+        // same ranks differ in lane bits 3..5.  Bit 3 is added up in registers (a rotation by 8 within the
+        // row of 16 lanes), the four rows go to LDS as they are: one atomic per rank, half and row
 #pragma unroll
         for (int m = 0; m < 2; ++m)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                int v = sums[m][h];
-#pragma unroll
-                for (int off = 8; off < 64; off <<= 1) v += __shfl_xor(v, off);
-                sums[m][h] = v;
-            }
-        if (lane < 8) {
+            for (int h = 0; h < 2; ++h)
+                sums[m][h] += __builtin_amdgcn_update_dpp(0, sums[m][h], 0x128 /* row_ror:8 */, 0xF, 0xF, false);
+        if ((lane & 8) == 0) {
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
                 atomicAdd(&csq[rk0 + m], sums[m][0]);
