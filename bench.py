@@ -558,8 +558,8 @@ def main():
 
 # HBM bytes per launch of the decode kernel on this workload from rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, scaled by a read kernel and a copy of known size); see
-# profiles/decode_4096x4096_n16_pmc.txt (39.15 MB fetched + 0.54 MB written; algorithmic 37.75 MB).
-TRAFFIC_BYTES_PER_LAUNCH = 39693000
+# profiles/decode_4096x4096_n16_pmc.txt (39.14 MB fetched + 0.54 MB written; algorithmic 37.75 MB).
+TRAFFIC_BYTES_PER_LAUNCH = 39682000
 
 if __name__ == "__main__":
     main()
