@@ -475,6 +475,13 @@ __global__ __launch_bounds__(512) void k_fused(KParams p) {
         m1 = magnitude(1, 1);
         apply(m0, 1, 0);
         apply(m1, 1, 1);
+        // left to itself the scheduler clusters the matrix-core instructions (two or three in a row, then
+        // runs of 30-40 vector instructions); one of them per nine vector instructions keeps both pipes fed
+#pragma unroll
+        for (int i = 0; i < 12; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one matrix-core instruction
+            __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);   // nine vector instructions
+        }
     };
 
     // ---- prologue: steps 0..2 on their way, chunk 0's activations and V(0) fragments ready
