@@ -163,6 +163,10 @@ __global__ __launch_bounds__(512, KSPLIT ? 4 : 1) void k_gemm(KParams p) {
     BS_GEMM_LOAD(A, 2)
     lds_barrier();
 
+    // The 128 x 256 tile has registers to spare (165 of 256): its fragments are read one step ahead of
+    // their use.  The other two tiles would spill with that (256 / 128 registers, 56 / 76 bytes of
+    // scratch: 8 % and 2x slower), so they read a step's fragments at its start.
+    constexpr bool kAhead = RJ == 2 && !KSPLIT;
     // One chunk from buffer BUF: at step 1 the chunk after it (already in registers T) goes to the
     // other buffer and the chunk two further on is requested, so every global load has two chunks
     // to arrive.  The barrier at the end makes the other buffer readable and protects this one
@@ -170,14 +174,28 @@ __global__ __launch_bounds__(512, KSPLIT ? 4 : 1) void k_gemm(KParams p) {
     // the second wavefront of the SIMD covers that latency.
 #define BS_GEMM_CHUNK(KC, BUF, S)                                                          \
     {                                                                                      \
+        v8h bn[RJ], an[2];                                                                 \
+        if constexpr (kAhead) {                                                            \
+            _Pragma("unroll") for (int j = 0; j < RJ; ++j) bn[j] = wfrag(BUF, 0, j);       \
+            _Pragma("unroll") for (int t = 0; t < 2; ++t) an[t] = xfrag(BUF, 0, t);        \
+        }                                                                                  \
         _Pragma("unroll") for (int s = 0; s < STEPS; ++s) {                                \
             if (s == 1) {                                                                  \
                 BS_GEMM_WRITE(S, (BUF) ^ 1)                                                \
                 BS_GEMM_LOAD(S, (KC) + 3)                                                  \
             }                                                                              \
             v8h b[RJ], a[2];                                                               \
-            _Pragma("unroll") for (int j = 0; j < RJ; ++j) b[j] = wfrag(BUF, s, j);        \
-            _Pragma("unroll") for (int t = 0; t < 2; ++t) a[t] = xfrag(BUF, s, t);         \
+            if constexpr (kAhead) {                                                        \
+                _Pragma("unroll") for (int j = 0; j < RJ; ++j) b[j] = bn[j];               \
+                _Pragma("unroll") for (int t = 0; t < 2; ++t) a[t] = an[t];                \
+                if (s + 1 < STEPS) {                                                       \
+                    _Pragma("unroll") for (int j = 0; j < RJ; ++j) bn[j] = wfrag(BUF, s + 1, j); \
+                    _Pragma("unroll") for (int t = 0; t < 2; ++t) an[t] = xfrag(BUF, s + 1, t);  \
+                }                                                                          \
+            } else {                                                                       \
+                _Pragma("unroll") for (int j = 0; j < RJ; ++j) b[j] = wfrag(BUF, s, j);    \
+                _Pragma("unroll") for (int t = 0; t < 2; ++t) a[t] = xfrag(BUF, s, t);     \
+            }                                                                              \
             __builtin_amdgcn_sched_barrier(0); /* requests before the step's arithmetic */ \
             _Pragma("unroll") for (int j = 0; j < RJ; ++j) {                               \
                 acc[j][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], b[j], acc[j][0], 0, 0, 0); \

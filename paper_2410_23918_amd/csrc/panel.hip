@@ -1084,14 +1084,14 @@ bool restore_fits(size_t block_stride, int n_loaded) {
 }
 
 // Estimated durations (microseconds, constants fitted to measurements).  k_fused: per round of
-// 256 workgroups ~8 us fixed + ~0.83 us per block and pair of column chunks of a workgroup; later
+// 256 workgroups ~8 us fixed + ~0.80 us per block and pair of column chunks of a workgroup; later
 // workgroups start as earlier ones end, so rounds beyond the first count fractionally.
 double fused_time_us(int out, int in, int batch, int n_loaded, int part_slots) {
     const int row_tiles = (out + 2 * kTileRows - 1) / (2 * kTileRows), chunk_pairs = (in / kChunkCols + 1) / 2;
     const int split = small_batch_split(out, in, batch, part_slots);
     const int wgs = row_tiles * ((batch + 31) / 32) * split;
     const double rounds = wgs <= 256 ? 1.0 : wgs / 256.0;
-    return rounds * (8.0 + 0.83 * n_loaded * ((chunk_pairs + split - 1) / split)) + (split > 1 ? 4.0 : 0.0);
+    return rounds * (8.0 + 0.80 * n_loaded * ((chunk_pairs + split - 1) / split)) + (split > 1 ? 4.0 : 0.0);
 }
 // k_tile: per pair of column chunks ~0.9 us per block for the rebuild + 12-14 us for the product
 // (14 when several token tiles of a row tile run at once, 6.5 up to 256 tokens, where only one
